@@ -1,0 +1,160 @@
+"""ctypes front end of the plain C oracle (oracle/gbnn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  Nothing in the product package imports it, and it imports nothing from
+the product package.  All arrays are numpy, on the host; W is the full byte matrix
+uint8[n][n] (W[j, i] = w_ji), activity is uint8[K][n].
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "gbnn_oracle.c"
+_LIB = _HERE / "libgbnn_oracle.so"
+
+RULES = {"sum_of_sum": 0, "sum_of_max": 1, "hybrid": 2, "sum_of_max_eq": 3}
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (a second or two)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               str(_SRC), "-o", str(_LIB)]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(str(_LIB))
+        u8p, i32p = ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_int32)
+        ci, i64 = ctypes.c_int, ctypes.c_int64
+        L.gbnn_oracle_store.restype = i64
+        L.gbnn_oracle_store.argtypes = [u8p, ci, ci, i32p, i64]
+        L.gbnn_oracle_sos_scores.restype = None
+        L.gbnn_oracle_sos_scores.argtypes = [u8p, ci, ci, u8p, ci, i32p]
+        L.gbnn_oracle_sos_select.restype = None
+        L.gbnn_oracle_sos_select.argtypes = [i32p, ci, ci, u8p]
+        L.gbnn_oracle_som_init.restype = None
+        L.gbnn_oracle_som_init.argtypes = [ci, ci, u8p]
+        L.gbnn_oracle_som_scores_eq.restype = None
+        L.gbnn_oracle_som_scores_eq.argtypes = [u8p, ci, ci, u8p, ci, i32p]
+        L.gbnn_oracle_som_pass_eq.restype = None
+        L.gbnn_oracle_som_pass_eq.argtypes = [u8p, ci, ci, u8p, ci, u8p]
+        L.gbnn_oracle_som_pass_boe.restype = None
+        L.gbnn_oracle_som_pass_boe.argtypes = [u8p, ci, ci, u8p, u8p, u8p]
+        L.gbnn_oracle_retrieve.restype = ci
+        L.gbnn_oracle_retrieve.argtypes = [u8p, ci, ci, u8p, u8p, i64, ci, ci, ci, i32p, ci]
+        _lib = L
+    return _lib
+
+
+def _u8(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def _i32(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def store(C: int, L: int, msgs: np.ndarray, W: np.ndarray | None = None):
+    """OR the cliques of msgs (int32[M][C]) into W (fresh zero matrix if None).
+    Returns (W uint8[n][n], number of skipped out-of-range messages)."""
+    n = C * L
+    if W is None:
+        W = np.zeros((n, n), dtype=np.uint8)
+    assert W.shape == (n, n) and W.dtype == np.uint8 and W.flags.c_contiguous
+    msgs = np.ascontiguousarray(msgs, dtype=np.int32).reshape(-1, C)
+    skipped = lib().gbnn_oracle_store(_u8(W), C, L, _i32(msgs), msgs.shape[0])
+    return W, int(skipped)
+
+
+def sos_scores(W, C, L, v, gamma):
+    v = np.ascontiguousarray(v, dtype=np.uint8)
+    s = np.zeros(C * L, dtype=np.int32)
+    lib().gbnn_oracle_sos_scores(_u8(W), C, L, _u8(v), gamma, _i32(s))
+    return s
+
+
+def sos_select(s, C, L):
+    s = np.ascontiguousarray(s, dtype=np.int32)
+    v = np.zeros(C * L, dtype=np.uint8)
+    lib().gbnn_oracle_sos_select(_i32(s), C, L, _u8(v))
+    return v
+
+
+def som_init(C, L, v):
+    v = np.array(v, dtype=np.uint8, copy=True)
+    lib().gbnn_oracle_som_init(C, L, _u8(v))
+    return v
+
+
+def som_scores_eq(W, C, L, v, gamma):
+    v = np.ascontiguousarray(v, dtype=np.uint8)
+    s = np.zeros(C * L, dtype=np.int32)
+    lib().gbnn_oracle_som_scores_eq(_u8(W), C, L, _u8(v), gamma, _i32(s))
+    return s
+
+
+def som_pass_eq(W, C, L, v, gamma):
+    v = np.ascontiguousarray(v, dtype=np.uint8)
+    out = np.zeros(C * L, dtype=np.uint8)
+    lib().gbnn_oracle_som_pass_eq(_u8(W), C, L, _u8(v), gamma, _u8(out))
+    return out
+
+
+def som_pass_boe(W, C, L, v, update_cluster=None):
+    v = np.ascontiguousarray(v, dtype=np.uint8)
+    out = np.zeros(C * L, dtype=np.uint8)
+    uc = None
+    if update_cluster is not None:
+        uc_arr = np.ascontiguousarray(update_cluster, dtype=np.uint8)
+        uc = _u8(uc_arr)
+    lib().gbnn_oracle_som_pass_boe(_u8(W), C, L, _u8(v), _u8(out), uc)
+    return out
+
+
+def retrieve(W, C, L, V0, rule, gamma=1, max_iters=20, nthreads=0):
+    """Retrieve K probes.  rule is a name from RULES.  Returns (V_out uint8[K][n],
+    iters int32[K] (+p converged at pass p, -max_iters cap reached), threads used)."""
+    n = C * L
+    V0 = np.ascontiguousarray(V0, dtype=np.uint8).reshape(-1, n)
+    K = V0.shape[0]
+    assert W.shape == (n, n) and W.dtype == np.uint8 and W.flags.c_contiguous
+    out = np.zeros_like(V0)
+    iters = np.zeros(K, dtype=np.int32)
+    if nthreads <= 0:
+        nthreads = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    used = lib().gbnn_oracle_retrieve(_u8(W), C, L, _u8(V0), _u8(out), K, RULES[rule], gamma, max_iters,
+                                      _i32(iters), nthreads)
+    return out, iters, int(used)
+
+
+def error_rate(V_out: np.ndarray, target_onehot: np.ndarray) -> float:
+    """Fraction of probes whose final activity is not exactly the one-hot code of the
+    message they were made from (retrieval rate of Section VII = 1 - this)."""
+    ok = (V_out == target_onehot).all(axis=1)
+    return 1.0 - float(ok.mean()) if len(ok) else 0.0
+
+
+def pack_bits(Wfull: np.ndarray) -> np.ndarray:
+    """Byte matrix -> the boundary's bit-packed layout uint32[n][ceil(n/32)] (bit j%32 of
+    word j//32 of row i is W[i, j], least significant bit first).  Used only to compare a
+    packed W coming from elsewhere with the oracle's."""
+    n = Wfull.shape[0]
+    nw = (n + 31) // 32
+    padded = np.zeros((n, nw * 32), dtype=np.uint8)
+    padded[:, :n] = Wfull
+    b = np.packbits(padded.reshape(n, nw, 32), axis=2, bitorder="little")  # [n][nw][4] bytes, LSB first
+    return b.view("<u4").reshape(n, nw)
