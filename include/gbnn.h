@@ -1,0 +1,116 @@
+/*
+ * gbnn.h -- C ABI of the MI355X (gfx950) library for batched retrieval in the Gripon-Berrou
+ * clustered associative memory, after Yao, Gripon, Rabbat, "A Massively Parallel Associative
+ * Memory Based on Sparse Neural Networks" (arXiv 1303.7032).
+ *
+ * Model (Section II-A): C clusters of L binary neurons, n = C*L; neuron (c,l) has flat index
+ * i = c*L + l (Section IV-B, 0-based here).  A message is C symbols in [0,L); it activates one
+ * neuron per cluster.  W is the n x n binary, symmetric adjacency with no edge inside a cluster.
+ *
+ * Conventions common to all calls
+ *   - Every pointer is a DEVICE pointer owned by the caller (e.g. a torch tensor's data_ptr()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on that stream and return; they never allocate, free or synchronise, and the library
+ *     keeps no state between calls.
+ *   - Return value: GBNN_OK (0) or a negative gbnn_status.  All argument checks happen on the
+ *     host before anything is enqueued; nothing is launched when an error is returned.
+ *   - W layout ("canonical"): uint32_t[n][nw], nw = ceil(n/32), row-major; bit (j % 32) of word
+ *     (j / 32) of row i is w_ij, least significant bit first; padding bits of the last word of
+ *     a row are zero.  W must be symmetric with all-zero intra-cluster blocks (what gbnn_store
+ *     produces); results for any other W are unspecified but memory-safe.
+ *   - Activity layout: uint8_t[K][n], probe k contiguous (column k of the paper's matrix V,
+ *     Section IV-B "Batch Retrieval"); each byte is 0 or 1 (only bit 0 of a byte is read).
+ *   - Limits: 2 <= C <= GBNN_MAX_C, L >= 1, n <= GBNN_MAX_N, 0 <= gamma <= GBNN_MAX_GAMMA,
+ *     max_iters >= 1, K >= 0, M >= 0.
+ */
+#ifndef GBNN_H
+#define GBNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GBNN_MAX_C 64
+#define GBNN_MAX_N 16384
+#define GBNN_MAX_GAMMA 32767
+
+/* Retrieval rules. */
+typedef enum {
+    GBNN_SUM_OF_SUM = 0, /* Eq. (3)-(5), Algorithm 1 */
+    GBNN_SUM_OF_MAX = 1, /* Eq. (6)-(7) in its bail-out-early form (Section IV-D, Theorem 1) */
+    GBNN_HYBRID = 2      /* the joint scheme, Algorithm 2 */
+} gbnn_rule;
+
+typedef enum {
+    GBNN_OK = 0,
+    GBNN_ERR_NULL = -1,      /* a required pointer is NULL */
+    GBNN_ERR_SHAPE = -2,     /* C, L, n, K or M outside the limits above */
+    GBNN_ERR_RULE = -3,      /* rule is not a gbnn_rule */
+    GBNN_ERR_GAMMA = -4,     /* gamma outside [0, GBNN_MAX_GAMMA] */
+    GBNN_ERR_ITERS = -5,     /* max_iters < 1 */
+    GBNN_ERR_WORKSPACE = -6, /* workspace NULL, misaligned (needs 256 bytes) or too small */
+    GBNN_ERR_DEVICE = -7     /* the HIP runtime refused a launch */
+} gbnn_status;
+
+/* Words per row of W: ceil(C*L/32).  0 if the shape is outside the limits. */
+size_t gbnn_w_row_words(int C, int L);
+/* Bytes of W: n * gbnn_w_row_words * 4.  0 if the shape is outside the limits. */
+size_t gbnn_w_bytes(int C, int L);
+/* Bytes of scratch device memory gbnn_retrieve needs for this shape, batch and rule (a
+ * multiple of 256, never 0 for a valid shape).  0 if an argument is outside the limits. */
+size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule);
+
+/*
+ * Storing (Section II-A): for every message, connect all pairs of its C active neurons, i.e.
+ * set w_ab = w_ba = 1 for a = c*L + m_c, b = c'*L + m_c', c != c'.  Bits are OR-ed into W, so
+ * W must be zeroed by the caller for an empty network and a later call adds more messages;
+ * the result does not depend on message order or repetition.
+ *   W      device, uint32_t[n][nw], read-modify-write
+ *   msgs   device, int32_t[M][C], 0-based symbols
+ *   status device int32_t or NULL; bit 0 is OR-ed in if some message had a symbol outside
+ *          [0,L); such a message is skipped entirely.  Zero it before the call.
+ */
+int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream);
+
+/*
+ * Retrieval of K probes, each independently, iterated until its activity vector is reproduced
+ * by a pass or max_iters passes have been made.
+ *   V0     device, uint8_t[K][n]; an erased cluster is all-zero for EVERY rule, the library
+ *          applies the rule's own initialisation: sum-of-sum and hybrid leave erased clusters
+ *          off (Section III-A, Algorithm 2 line 1), sum-of-max turns them all on (Section III-C).
+ *   V_out  device, uint8_t[K][n], the last activity vector computed; may be the same pointer as
+ *          V0 (in place), must not overlap it otherwise.
+ *   rule   GBNN_SUM_OF_SUM: s_i = gamma*v_i + sum_j w_ji v_j, then per cluster every neuron
+ *            reaching the cluster maximum stays on (ties and an all-zero maximum included).
+ *          GBNN_SUM_OF_MAX: v_i stays on iff it is on and every other cluster holds an active
+ *            neighbour of i (score gamma + C - 1 with gamma = 1; `gamma` is ignored).
+ *          GBNN_HYBRID: pass 1 keeps, in the clusters that are all-zero in the probe (e of
+ *            them), the neurons whose sum-of-sum score is exactly C - e; later passes apply the
+ *            sum-of-max update to those clusters only; `gamma` is ignored.
+ *   max_iters  cap on the number of passes (the hybrid's first pass counts).
+ *   iters_out  device int32_t[K] or NULL: +p if pass p reproduced its input (the confirming
+ *          pass counts; for the hybrid the test is made from pass 2 on), -max_iters if the cap
+ *          was reached first.
+ *   workspace  device scratch, 256-byte aligned, at least gbnn_workspace_bytes(...) bytes;
+ *          contents are undefined before and after the call.  Two calls that overlap in time
+ *          must not share it.
+ */
+int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
+                  int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* Static description of a status code (never NULL). */
+const char *gbnn_strerror(int code);
+
+/* Name of the kernel family gbnn_retrieve would run for this shape, rule and pointer alignment
+ * ("wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
+ * "generic" = any shape), or NULL for invalid arguments.  Host only; for tests and reports. */
+const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GBNN_H */

@@ -1,0 +1,153 @@
+"""Thin Python binding of the C ABI in include/gbnn.h (argument marshalling only).
+
+Every step of storing and retrieval runs in the HIP kernels of libgbnn_hip.so; torch is
+used for device memory and streams.  There is no CPU fallback: if the library has not been
+built (python -m paper_1303_7032_amd.build) loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libgbnn_hip.so"
+_lib = None
+
+SUM_OF_SUM, SUM_OF_MAX, HYBRID = 0, 1, 2
+RULES = {"sum_of_sum": SUM_OF_SUM, "sum_of_max": SUM_OF_MAX, "hybrid": HYBRID}
+
+GBNN_OK = 0
+ERRORS = {"NULL": -1, "SHAPE": -2, "RULE": -3, "GAMMA": -4, "ITERS": -5, "WORKSPACE": -6, "DEVICE": -7}
+
+
+class GbnnError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"gbnn status {code}: {message}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Load libgbnn_hip.so (once).  Raises if it is not built."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_1303_7032_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        vp, ci, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        L.gbnn_w_row_words.restype = sz
+        L.gbnn_w_row_words.argtypes = [ci, ci]
+        L.gbnn_w_bytes.restype = sz
+        L.gbnn_w_bytes.argtypes = [ci, ci]
+        L.gbnn_workspace_bytes.restype = sz
+        L.gbnn_workspace_bytes.argtypes = [ci, ci, i64, ci]
+        L.gbnn_store.restype = ci
+        L.gbnn_store.argtypes = [vp, ci, ci, vp, i64, vp, vp]
+        L.gbnn_retrieve.restype = ci
+        L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
+        L.gbnn_strerror.restype = ctypes.c_char_p
+        L.gbnn_strerror.argtypes = [ci]
+        L.gbnn_retrieve_path.restype = ctypes.c_char_p
+        L.gbnn_retrieve_path.argtypes = [ci, ci, ci, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(code: int) -> None:
+    if code != GBNN_OK:
+        raise GbnnError(code, lib().gbnn_strerror(code).decode())
+
+
+def _rule(rule) -> int:
+    return RULES[rule] if isinstance(rule, str) else int(rule)
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> None:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+
+
+def gbnn_w_row_words(C: int, L: int) -> int:
+    return int(lib().gbnn_w_row_words(C, L))
+
+
+def gbnn_w_bytes(C: int, L: int) -> int:
+    return int(lib().gbnn_w_bytes(C, L))
+
+
+def gbnn_workspace_bytes(C: int, L: int, K: int, rule) -> int:
+    return int(lib().gbnn_workspace_bytes(C, L, K, _rule(rule)))
+
+
+def gbnn_strerror(code: int) -> str:
+    return lib().gbnn_strerror(code).decode()
+
+
+def new_network(C: int, L: int, device="cuda") -> torch.Tensor:
+    """An empty (all-zero) W in the canonical layout: int32[n][ceil(n/32)] on the device."""
+    nw = gbnn_w_row_words(C, L)
+    if nw == 0:
+        _check(ERRORS["SHAPE"])
+    return torch.zeros((C * L, nw), dtype=torch.int32, device=device)
+
+
+def gbnn_store(W: torch.Tensor, C: int, L: int, msgs: torch.Tensor, status: torch.Tensor | None = None) -> None:
+    """OR the cliques of msgs (int32[M][C] on the device) into W (enqueued on the current stream)."""
+    _dev(W, torch.int32, "W")
+    _dev(msgs, torch.int32, "msgs")
+    if W.numel() * 4 != gbnn_w_bytes(C, L) or msgs.numel() % C:
+        _check(ERRORS["SHAPE"])
+    st = 0
+    if status is not None:
+        _dev(status, torch.int32, "status")
+        st = status.data_ptr()
+    M = msgs.numel() // C
+    _check(lib().gbnn_store(W.data_ptr(), C, L, msgs.data_ptr() if M else 0, M, st, _stream(W)))
+
+
+def gbnn_retrieve(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma: int = 1, max_iters: int = 20,
+                  V_out: torch.Tensor | None = None, iters_out: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None, want_iters: bool = True):
+    """Retrieve the K probes of V0 (uint8[K][n]).  Returns (V_out, iters_out).
+
+    Output tensors and the workspace are allocated with torch when not supplied (pass them
+    in to keep allocation out of a timed loop).  Work is enqueued on the current stream.
+    """
+    r = _rule(rule)
+    _dev(W, torch.int32, "W")
+    _dev(V0, torch.uint8, "V0")
+    n = C * L
+    if W.numel() * 4 != gbnn_w_bytes(C, L) or V0.numel() % n:
+        _check(ERRORS["SHAPE"])
+    K = V0.numel() // n
+    if V_out is None:
+        V_out = torch.empty_like(V0)
+    _dev(V_out, torch.uint8, "V_out")
+    if V_out.numel() != V0.numel():
+        _check(ERRORS["SHAPE"])
+    if iters_out is None and want_iters:
+        iters_out = torch.empty(K, dtype=torch.int32, device=V0.device)
+    if iters_out is not None:
+        _dev(iters_out, torch.int32, "iters_out")
+        if iters_out.numel() != K:
+            _check(ERRORS["SHAPE"])
+    need = gbnn_workspace_bytes(C, L, K, r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=V0.device)
+    _dev(workspace, torch.uint8, "workspace")
+    _check(lib().gbnn_retrieve(W.data_ptr(), C, L, V0.data_ptr() if K else 0, V_out.data_ptr() if K else 0, K, r,
+                               gamma, max_iters, iters_out.data_ptr() if iters_out is not None else 0,
+                               workspace.data_ptr(), workspace.numel(), _stream(V0)))
+    return V_out, iters_out
+
+
+def gbnn_retrieve_path(C: int, L: int, rule, V0: torch.Tensor | None = None, V_out: torch.Tensor | None = None) -> str:
+    p = lib().gbnn_retrieve_path(C, L, _rule(rule), V0.data_ptr() if V0 is not None else 0,
+                                 V_out.data_ptr() if V_out is not None else 0)
+    return p.decode() if p else ""

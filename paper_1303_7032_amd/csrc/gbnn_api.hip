@@ -1,0 +1,128 @@
+// Host side of the C ABI declared in include/gbnn.h: argument checks and kernel dispatch.
+#include <cstdlib>
+
+#include "gbnn_internal.h"
+
+using namespace gbnn;
+
+namespace {
+
+bool shape_ok(int C, int L)
+{
+    if (C < 2 || C > GBNN_MAX_C || L < 1) return false;
+    const int64_t n = (int64_t)C * (int64_t)L;
+    return n <= GBNN_MAX_N;
+}
+
+bool rule_ok(int rule) { return rule == GBNN_SUM_OF_SUM || rule == GBNN_SUM_OF_MAX || rule == GBNN_HYBRID; }
+
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Words per lane of the one-wave-per-probe kernel, or 0 for the any-shape kernel.
+int pick_path(int C, int L, const void *V0, const void *Vout)
+{
+    const char *force = std::getenv("GBNN_FORCE_GENERIC");
+    if (force && force[0] == '1') return 0;
+    if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;
+    return wave_words_per_lane(C, L);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gbnn_w_row_words(int C, int L)
+{
+    if (!shape_ok(C, L)) return 0;
+    return (size_t)((C * L + 31) / 32);
+}
+
+size_t gbnn_w_bytes(int C, int L)
+{
+    if (!shape_ok(C, L)) return 0;
+    return (size_t)C * (size_t)L * gbnn_w_row_words(C, L) * sizeof(uint32_t);
+}
+
+size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule)
+{
+    if (!shape_ok(C, L) || K < 0 || !rule_ok(rule)) return 0;
+    return round256(workspace_has_bytes(C, (int)gbnn_w_row_words(C, L))) + 256;
+}
+
+int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream)
+{
+    if (!shape_ok(C, L) || M < 0) return GBNN_ERR_SHAPE;
+    if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
+    const hipError_t e =
+        launch_store(W, C, L, (int)gbnn_w_row_words(C, L), msgs, M, status, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
+                  int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
+                  void *stream)
+{
+    if (!shape_ok(C, L) || K < 0) return GBNN_ERR_SHAPE;
+    if (!rule_ok(rule)) return GBNN_ERR_RULE;
+    if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
+    if (max_iters < 1) return GBNN_ERR_ITERS;
+    if (!W || (K > 0 && (!V0 || !V_out))) return GBNN_ERR_NULL;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < gbnn_workspace_bytes(C, L, K, rule))
+        return GBNN_ERR_WORKSPACE;
+    if (K == 0) return GBNN_OK;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    RetrieveArgs a;
+    a.W = W;
+    a.has = static_cast<const uint32_t *>(workspace);
+    a.V0 = V0;
+    a.Vout = V_out;
+    a.iters = iters_out;
+    a.K = K;
+    a.C = C;
+    a.L = L;
+    a.n = C * L;
+    a.nw = (int)gbnn_w_row_words(C, L);
+    a.rule = rule;
+    a.gamma = gamma;
+    a.max_iters = max_iters;
+
+    // The summary rows are what a fully active cluster contributes (sum-of-max initialisation);
+    // the other two rules never see a fully active cluster through it unless L is tiny, but the
+    // kernels consult the table whenever a cluster is full, so it is always built.
+    hipError_t e = launch_cluster_summary(W, C, L, a.nw, static_cast<uint32_t *>(workspace), s);
+    if (e != hipSuccess) return GBNN_ERR_DEVICE;
+    const int wpl = pick_path(C, L, V0, V_out);
+    e = wpl ? launch_retrieve_wave(a, wpl, s) : launch_retrieve_generic(a, s);
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+const char *gbnn_strerror(int code)
+{
+    switch (code) {
+    case GBNN_OK: return "ok";
+    case GBNN_ERR_NULL: return "a required pointer is NULL";
+    case GBNN_ERR_SHAPE: return "shape outside the limits (2 <= C <= 64, L >= 1, C*L <= 16384, K >= 0, M >= 0)";
+    case GBNN_ERR_RULE: return "unknown retrieval rule";
+    case GBNN_ERR_GAMMA: return "gamma outside [0, 32767]";
+    case GBNN_ERR_ITERS: return "max_iters must be at least 1";
+    case GBNN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than gbnn_workspace_bytes";
+    case GBNN_ERR_DEVICE: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status code";
+    }
+}
+
+const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out)
+{
+    if (!shape_ok(C, L) || !rule_ok(rule)) return nullptr;
+    switch (pick_path(C, L, V0, V_out)) {
+    case 1: return "wave1";
+    case 2: return "wave2";
+    case 4: return "wave4";
+    default: return "generic";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+// Storing messages as cliques (Section II-A) and the per-cluster summary rows of W.
+#include "gbnn_internal.h"
+
+namespace gbnn {
+namespace {
+
+// One thread per (message m, cluster c): validates the message, then sets, in the row of the
+// active neuron of cluster c, the bits of the message's active neurons of all other clusters.
+// Bit sets are idempotent atomic ORs, so the result is independent of thread order.
+__global__ __launch_bounds__(256) void k_store(uint32_t *W, int C, int L, int nw,
+                                               const int32_t *__restrict__ msgs, int64_t M,
+                                               int32_t *__restrict__ status)
+{
+    const int64_t total = M * C;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t m = t / C;
+        const int c = (int)(t - m * C);
+        const int32_t *sym = msgs + m * C;
+        bool ok = true;
+        for (int c2 = 0; c2 < C; ++c2) {
+            const int32_t s = sym[c2];
+            ok = ok && (s >= 0) && (s < L);
+        }
+        if (!ok) {
+            if (c == 0 && status) atomicOr(status, 1);
+            continue;
+        }
+        uint32_t *row = W + ((int64_t)c * L + sym[c]) * nw;
+        for (int c2 = 0; c2 < C; ++c2) {
+            if (c2 == c) continue;
+            const int col = c2 * L + sym[c2];
+            const uint32_t bit = 1u << (col & 31);
+            uint32_t *p = row + (col >> 5);
+            // A stale read can only cause a redundant OR, never a missed one.
+            if (!(*p & bit)) atomicOr(p, bit);
+        }
+    }
+}
+
+// Cluster summary: has[c][w] = OR over the L rows j of cluster c of W[j][w], i.e. bit i says that
+// neuron i has at least one neighbour in cluster c.  It is what a fully active cluster (the
+// sum-of-max initialisation of an erased cluster, Section III-C) contributes in one pass.
+// Block = (cluster c, 64 consecutive words), 1024 threads = 16 row subsets x 64 words.
+constexpr int kSumRows = 16;
+__global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_t *__restrict__ W, int C, int L,
+                                                                   int nw, uint32_t *__restrict__ has)
+{
+    __shared__ uint32_t part[kSumRows][64];
+    const int c = blockIdx.y;
+    const int wl = threadIdx.x & 63;
+    const int r = threadIdx.x >> 6;
+    const int w = blockIdx.x * 64 + wl;
+    uint32_t acc = 0;
+    if (w < nw) {
+        const uint32_t *base = W + (int64_t)c * L * nw + w;
+        for (int l = r; l < L; l += kSumRows) acc |= base[(int64_t)l * nw];
+    }
+    part[r][wl] = acc;
+    __syncthreads();
+    if (r == 0 && w < nw) {
+        for (int k = 1; k < kSumRows; ++k) acc |= part[k][wl];
+        has[(int64_t)c * nw + w] = acc;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
+                        hipStream_t s)
+{
+    if (M == 0) return hipSuccess;
+    const int64_t total = M * C;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_store, dim3((unsigned)blocks), dim3(256), 0, s, W, C, L, nw, msgs, M, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_cluster_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has, hipStream_t s)
+{
+    dim3 grid((unsigned)((nw + 63) / 64), (unsigned)C);
+    hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
+    return hipGetLastError();
+}
+
+}  // namespace gbnn

@@ -1,0 +1,270 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, bit for bit.
+
+Everything here is integer / bit work, so the bar is exact equality: the packed W, every byte
+of every final activity vector, every entry of iters_out, and the retrieval error rate.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gbnn_oracle as orc
+from paper_1303_7032_amd import binding as gb
+from paper_1303_7032_amd import inputs
+from conftest import read_golden
+
+pytestmark = pytest.mark.gpu
+
+RULES = ("sum_of_sum", "sum_of_max", "hybrid")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    gb.lib()  # fails loudly if the HIP library is not built
+
+
+def dev_store(C, L, msgs):
+    W = gb.new_network(C, L)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gb.gbnn_store(W, C, L, torch.from_numpy(np.ascontiguousarray(msgs, dtype=np.int32)).cuda(), status)
+    return W, int(status.item())
+
+
+def dev_retrieve(W, C, L, V0, rule, gamma, cap, force_generic=False, **kw):
+    old = os.environ.get("GBNN_FORCE_GENERIC")
+    os.environ["GBNN_FORCE_GENERIC"] = "1" if force_generic else "0"
+    try:
+        V0d = torch.from_numpy(V0).cuda() if isinstance(V0, np.ndarray) else V0
+        out, it = gb.gbnn_retrieve(W, C, L, V0d, rule, gamma, cap, **kw)
+        torch.cuda.synchronize()
+    finally:
+        if old is None:
+            os.environ.pop("GBNN_FORCE_GENERIC", None)
+        else:
+            os.environ["GBNN_FORCE_GENERIC"] = old
+    return out.cpu().numpy(), it.cpu().numpy()
+
+
+def check_same(out, it, ref, itref, what):
+    bad = np.nonzero((out != ref).any(axis=1))[0]
+    assert bad.size == 0, f"{what}: {bad.size} probes differ, first {bad[:5]}"
+    badi = np.nonzero(it != itref)[0]
+    assert badi.size == 0, f"{what}: iters differ at {badi[:5]}: {it[badi[:5]]} vs {itref[badi[:5]]}"
+
+
+# ------------------------------------------------------------------------------- storing
+@pytest.mark.parametrize("name", list(inputs.WORKLOADS))
+def test_store_bit_exact(name):
+    w = inputs.WORKLOADS[name]
+    msgs = w.messages()
+    Wd, st = dev_store(w.C, w.L, msgs)
+    Wo, skipped = orc.store(w.C, w.L, msgs)
+    assert st == 0 and skipped == 0
+    got = Wd.cpu().numpy().view(np.uint32)
+    assert (got == orc.pack_bits(Wo)).all()
+
+
+@pytest.mark.parametrize("C,L,M", [(3, 3, 4), (5, 12, 200), (7, 33, 500), (2, 1, 3), (64, 256, 3000)])
+def test_store_odd_shapes_incremental_and_status(C, L, M):
+    msgs = inputs.make_messages(C, L, M, 17)
+    Wo, _ = orc.store(C, L, msgs)
+    # two calls, second one overlapping the first, plus messages with bad symbols
+    bad = msgs[:3].copy()
+    bad[0, 0] = L
+    bad[1, C - 1] = -1
+    W = gb.new_network(C, L)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    h = M // 2
+    for part in (msgs[:h], msgs[h // 2:], bad[:2]):
+        gb.gbnn_store(W, C, L, torch.from_numpy(np.ascontiguousarray(part)).cuda(), status)
+    assert int(status.item()) == 1
+    assert (W.cpu().numpy().view(np.uint32) == orc.pack_bits(Wo)).all()
+    gb.gbnn_store(W, C, L, torch.zeros((0, C), dtype=torch.int32, device="cuda"))  # M = 0 is a no-op
+
+
+# ------------------------------------------------------------------------------- worked example
+def test_oscillation_example_through_the_abi():
+    """Section V-A on the GPU (n = 9, any-shape kernel): printed v^1..v^3 and the cap path."""
+    g = read_golden("oscillation_example.txt")
+    C, L = int(g["C"][0]), int(g["L"][0])
+    msgs = np.array([[int(x) - 1 for x in m.split()] for m in g["messages_1based"][0].split("/")], dtype=np.int32)
+    vec = {k: np.array([int(x) for x in g[k][0].split()], dtype=np.uint8) for k in ("v0", "v1", "v2", "v3")}
+    W, _ = dev_store(C, L, msgs)
+    for cap, want in {1: "v1", 2: "v2", 3: "v3", 4: "v2", 9: "v1"}.items():
+        out, it = dev_retrieve(W, C, L, vec["v0"][None, :].copy(), "sum_of_sum", 1, cap)
+        assert (out[0] == vec[want]).all() and it[0] == -cap
+    out, it = dev_retrieve(W, C, L, vec["v0"][None, :].copy(), "sum_of_sum", 2, 20)
+    assert (out[0] == vec["v2"]).all() and it[0] == 3
+    out, it = dev_retrieve(W, C, L, vec["v0"][None, :].copy(), "sum_of_max", 1, 20)
+    assert (out[0] == vec["v1"]).all() and it[0] == 1
+    out, it = dev_retrieve(W, C, L, vec["v0"][None, :].copy(), "hybrid", 1, 20)
+    assert (out[0] == vec["v1"]).all() and it[0] == 2
+
+
+# ------------------------------------------------------------------------------- small / medium shapes
+SHAPES = [
+    # C, L, M, e, K
+    (4, 16, 50, 2, 200),     # cfg1
+    (3, 3, 4, 2, 37),        # clusters inside one word
+    (5, 12, 200, 2, 101),    # clusters straddle words
+    (7, 33, 400, 3, 64),     # n = 231, not a multiple of 32
+    (8, 32, 300, 4, 259),    # one word per cluster, ragged K
+    (8, 128, 5000, 4, 515),  # cfg2 shape: half the lanes idle
+    (8, 256, 20000, 4, 1027),  # cfg3 shape: several workgroups and a ragged tail
+    (3, 256, 3000, 1, 130),  # 24 of 64 lanes
+    (12, 256, 20000, 6, 300),  # 96 words: two words per lane, second slot half empty
+    (16, 512, 100000, 8, 260),  # cfg5 shape: four words per lane
+    (2, 2048, 3000, 1, 70),  # a cluster is a whole wave
+    (16, 1024, 60000, 8, 20),  # n = 16384: the largest shape, any-shape kernel
+]
+
+
+@pytest.fixture(scope="module")
+def networks():
+    cache = {}
+
+    def get(C, L, M):
+        key = (C, L, M)
+        if key not in cache:
+            msgs = inputs.make_messages(C, L, M, 1000 + C * L + M)
+            Wo, _ = orc.store(C, L, msgs)
+            Wd, _ = dev_store(C, L, msgs)
+            assert (Wd.cpu().numpy().view(np.uint32) == orc.pack_bits(Wo)).all()
+            cache[key] = (msgs, Wo, Wd)
+        return cache[key]
+    return get
+
+
+@pytest.mark.parametrize("C,L,M,e,K", SHAPES)
+@pytest.mark.parametrize("rule", RULES)
+def test_probes_from_stored_messages(networks, C, L, M, e, K, rule):
+    msgs, Wo, Wd = networks(C, L, M)
+    q, er = inputs.make_probe_plan(C, M, K, e, 5 + C + L)
+    V0 = inputs.one_hot(msgs[q], L, er)
+    for gamma, cap in ((1, 20), (2, 3)):
+        ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
+        out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap)
+        check_same(out, it, ref, itref, f"{rule} gamma={gamma} cap={cap}")
+        if gb.gbnn_retrieve_path(C, L, rule, torch.zeros(1, device="cuda")) != "generic" and K <= 300:
+            out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, force_generic=True)
+            check_same(out, it, ref, itref, f"{rule} generic gamma={gamma} cap={cap}")
+        if rule != "sum_of_sum":
+            break  # gamma is ignored by the other rules
+
+
+@pytest.mark.parametrize("C,L,M", [(4, 16, 50), (5, 12, 200), (8, 32, 300), (8, 128, 5000), (8, 256, 20000),
+                                    (16, 512, 100000)])
+@pytest.mark.parametrize("rule", RULES)
+def test_arbitrary_binary_probes(networks, C, L, M, rule):
+    """Probes outside the one-active-neuron-per-cluster contract: several active neurons in a
+    cluster, corrupted symbols, empty and full probes, random dense activity."""
+    msgs, Wo, Wd = networks(C, L, M)
+    n = C * L
+    rng = np.random.default_rng(C * 1000 + L)
+    rows = []
+    base = inputs.one_hot(msgs[:8], L)
+    rows += [base[0], np.zeros(n, np.uint8), np.ones(n, np.uint8)]
+    for k in range(8):                                  # two stored messages superposed, some clusters erased
+        v = base[k] | base[(k + 3) % 8]
+        v.reshape(C, L)[rng.permutation(C)[: C // 2]] = 0
+        rows.append(v)
+    for k in range(6):                                  # a corrupted symbol
+        v = base[k].copy().reshape(C, L)
+        c = int(rng.integers(C))
+        v[c] = 0
+        v[c, int(rng.integers(L))] = 1
+        v[(c + 1) % C] = 0
+        rows.append(v.reshape(-1))
+    for dens in (1.0 / L, 4.0 / L, 0.2, 0.7):           # random activity
+        for _ in range(3):
+            rows.append((rng.random(n) < dens).astype(np.uint8))
+    v = np.ones(n, np.uint8)                            # one cluster partly on, the rest full
+    v[: L // 2] = 0
+    rows.append(v)
+    V0 = np.stack(rows)
+    for gamma, cap in ((1, 6), (0, 4), (5, 4)):
+        ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
+        out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap)
+        check_same(out, it, ref, itref, f"{rule} gamma={gamma}")
+        out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, force_generic=True)
+        check_same(out, it, ref, itref, f"{rule} generic gamma={gamma}")
+        if rule != "sum_of_sum":
+            break
+
+
+def test_edge_cases(networks):
+    C, L, M = 8, 256, 20000
+    msgs, Wo, Wd = networks(C, L, M)
+    n = C * L
+    # K = 0
+    out, it = gb.gbnn_retrieve(Wd, C, L, torch.zeros((0, n), dtype=torch.uint8, device="cuda"), "sum_of_max")
+    assert out.numel() == 0 and it.numel() == 0
+    for e in (0, 1, C - 1, C):
+        q, er = inputs.make_probe_plan(C, M, 33, e, 9)
+        V0 = inputs.one_hot(msgs[q], L, er)
+        for rule in RULES:
+            for cap in (1, 2, 20):
+                ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, 1, cap)
+                out, it = dev_retrieve(Wd, C, L, V0, rule, 1, cap)
+                check_same(out, it, ref, itref, f"e={e} {rule} cap={cap}")
+    # in place, without iters_out; then through an unaligned view (any-shape kernel)
+    q, er = inputs.make_probe_plan(C, M, 77, 4, 10)
+    V0 = inputs.one_hot(msgs[q], L, er)
+    ref, itref, _ = orc.retrieve(Wo, C, L, V0, "sum_of_max", 1, 20)
+    buf = torch.from_numpy(V0).cuda()
+    gb.gbnn_retrieve(Wd, C, L, buf, "sum_of_max", 1, 20, V_out=buf, want_iters=False)
+    assert (buf.cpu().numpy() == ref).all()
+    raw = torch.zeros(V0.size + 64, dtype=torch.uint8, device="cuda")
+    view = raw[3:3 + V0.size].view(77, n)
+    view.copy_(torch.from_numpy(V0))
+    assert gb.gbnn_retrieve_path(C, L, "hybrid", view, view) == "generic"
+    refh, ith, _ = orc.retrieve(Wo, C, L, V0, "hybrid", 1, 20)
+    out, it = gb.gbnn_retrieve(Wd, C, L, view, "hybrid", 1, 20, V_out=view)
+    torch.cuda.synchronize()
+    check_same(out.cpu().numpy(), it.cpu().numpy(), refh, ith, "unaligned in place")
+    assert int(raw[:3].sum()) == 0 and int(raw[3 + V0.size:].sum()) == 0
+
+
+def test_argument_errors_reach_python():
+    W = gb.new_network(4, 16)
+    V = torch.zeros((2, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(gb.GbnnError) as ei:
+        gb.gbnn_retrieve(W, 4, 16, V, "sum_of_max", 1, 0)
+    assert ei.value.code == gb.ERRORS["ITERS"]
+    with pytest.raises(gb.GbnnError) as ei:
+        gb.gbnn_retrieve(W, 4, 16, V, "sum_of_sum", -1, 4)
+    assert ei.value.code == gb.ERRORS["GAMMA"]
+    with pytest.raises(gb.GbnnError) as ei:
+        gb.gbnn_retrieve(W, 4, 16, V, 7, 1, 4)
+    assert ei.value.code == gb.ERRORS["RULE"]
+    with pytest.raises(gb.GbnnError) as ei:
+        gb.gbnn_retrieve(W, 4, 16, V, "hybrid", 1, 4, workspace=torch.zeros(256, dtype=torch.uint8, device="cuda")[:16])
+    assert ei.value.code == gb.ERRORS["WORKSPACE"]
+
+
+# ------------------------------------------------------------------------------- the five configurations, full size
+@pytest.mark.parametrize("name", list(inputs.WORKLOADS))
+def test_full_configuration(name):
+    """BASELINE configurations at full K, in the launch configuration the benchmark times:
+    identical W, identical final activity for every probe, identical iters and error rate."""
+    w = inputs.WORKLOADS[name]
+    msgs = w.messages()
+    Wo, _ = orc.store(w.C, w.L, msgs)
+    Wd, _ = dev_store(w.C, w.L, msgs)
+    assert (Wd.cpu().numpy().view(np.uint32) == orc.pack_bits(Wo)).all()
+    q, er, V0 = w.probes(msgs)
+    target = inputs.one_hot(msgs[q], w.L)
+    V0d = torch.from_numpy(V0).cuda()
+    finals = {}
+    for rule in w.rules:
+        print(f"[{name}] {rule}: oracle on {w.K} probes", flush=True)
+        ref, itref, _ = orc.retrieve(Wo, w.C, w.L, V0, rule, w.gamma, w.max_iters)
+        out, it = dev_retrieve(Wd, w.C, w.L, V0d, rule, w.gamma, w.max_iters)
+        check_same(out, it, ref, itref, f"{name} {rule}")
+        assert orc.error_rate(out, target) == orc.error_rate(ref, target)
+        finals[rule] = out
+        del ref
+    if "hybrid" in finals and "sum_of_max" in finals:
+        assert (finals["hybrid"] == finals["sum_of_max"]).all()      # Theorem 4
