@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark: retrieved queries per second at c=8, l=256 (sum-of-max and hybrid), one MI355X.
+
+A step is one sweep of the retrieval hot path over one batch of K device-resident probes:
+one gbnn_retrieve call with the sum-of-max rule and one with the hybrid rule (probe load and
+rule initialisation, scoring, per-cluster selection, iteration to the fixed point or the cap,
+result store).  value = 2*K*steps / elapsed.  Storing the messages (the feeder) is timed
+separately and is not part of value; neither are host<->device copies: probes and results stay
+in HBM.  Inputs are seeded synthetic uniform-random messages, the paper's own workload.
+
+The same JSON line carries the roofline of the dominant kernel (HIP events recorded on the
+launch stream around every call inside the timed region) and the CPU oracle timed on the host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_probe(n: int, K: int, with_iters: bool) -> float:
+    """Read the probe once, write the result once, read W once per batch (+ the pass count)."""
+    return 2.0 * n + (n * n / 8.0) / K + (4.0 if with_iters else 0.0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3", help="cfg3 (default), cfg4_m10k, cfg4_m30k, cfg4_m50k, cfg5, cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed per-workload side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (probes are independent, so more GPUs would just "
+              "shard the batch with no exchange); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_1303_7032_amd import binding as gb
+    from paper_1303_7032_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    gb.lib()
+    w = inputs.WORKLOADS[args.workload]
+    C, L, n, K = w.C, w.L, w.n, w.K
+    rules = [r for r in ("sum_of_max", "hybrid", "sum_of_sum") if r in w.rules]
+
+    # ---- inputs, resident in HBM before anything is timed
+    msgs = w.messages()
+    q, er, V0 = w.probes(msgs)
+    msgs_d = torch.from_numpy(msgs).cuda()
+    V0d = torch.from_numpy(V0).cuda()
+    W = gb.new_network(C, L)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    gb.gbnn_store(W, C, L, msgs_d)
+    torch.cuda.synchronize()
+    store_s = time.perf_counter() - t0
+
+    outs = {r: torch.empty_like(V0d) for r in rules}
+    iters = {r: torch.empty(K, dtype=torch.int32, device="cuda") for r in rules}
+    ws = torch.empty(gb.gbnn_workspace_bytes(C, L, K, rules[0]), dtype=torch.uint8, device="cuda")
+
+    def call(rule):
+        gb.gbnn_retrieve(W, C, L, V0d, rule, w.gamma, w.max_iters, V_out=outs[rule], iters_out=iters[rule],
+                         workspace=ws)
+
+    for _ in range(args.warmup):
+        for r in rules:
+            call(r)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, HIP events around every call on the launch stream
+    ev = {r: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)] for r in rules}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for r in rules:
+            a, b = ev[r][s]
+            a.record()
+            call(r)
+            b.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    queries_per_step = K * len(rules)
+    value = queries_per_step * args.steps / elapsed
+
+    per_rule = {}
+    abytes = algorithmic_bytes_per_probe(n, K, True) * K
+    for r in rules:
+        ms = np.array([a.elapsed_time(b) for a, b in ev[r]])
+        per_rule[r] = {"ms_avg": float(ms.mean()), "ms_min": float(ms.min()), "qps": K / (ms.mean() * 1e-3),
+                       "hbm_GBs": abytes / (ms.mean() * 1e-3) / 1e9}
+    dominant = max(rules, key=lambda r: per_rule[r]["ms_avg"])
+    achieved = per_rule[dominant]["hbm_GBs"]
+    traffic = None
+    tfile = ROOT / "profiles" / "hbm_traffic.json"
+    if tfile.exists():
+        traffic = json.loads(tfile.read_text()).get(f"{args.workload}:{dominant}")
+
+    # ---- outcome of the retrieval (outside the timed region)
+    target_idx = torch.from_numpy(inputs.active_neurons(msgs[q], L)).cuda()
+    stats = {}
+    for r in rules:
+        o = outs[r].view(K, n)
+        ok = (o.sum(dim=1, dtype=torch.int32) == C) & (o.gather(1, target_idx).sum(dim=1, dtype=torch.int32) == C)
+        it = iters[r]
+        stats[r] = {"error_rate": 1.0 - float(ok.float().mean()), "mean_passes": float(it.abs().float().mean()),
+                    "capped": int((it < 0).sum())}
+        per_rule[r].update(stats[r])
+
+    # ---- CPU oracle on the host cores (a reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gbnn_oracle as orc
+        Wo, _ = orc.store(C, L, msgs)
+        Ks = min(K, 65536)
+        refs = {}
+        used = 1
+        t0 = time.perf_counter()
+        for r in rules:
+            refs[r] = orc.retrieve(Wo, C, L, V0[:Ks], r, w.gamma, w.max_iters)
+            used = refs[r][2]
+        cpu_s = time.perf_counter() - t0
+        for r in rules:  # untimed: the GPU results of the timed region against the oracle's
+            ref, itref, _ = refs[r]
+            per_rule[r]["matches_oracle_on_sample"] = bool(
+                (outs[r][:Ks].cpu().numpy() == ref).all() and (iters[r][:Ks].cpu().numpy() == itref).all())
+        cpu = {"value": Ks * len(rules) / cpu_s, "unit": "queries/s", "cores": used, "kind": "oracle",
+               "sample": f"first {Ks} probes of the batch, rules {'+'.join(rules)}, {cpu_s:.2f} s wall on {used} threads"}
+
+    line = {
+        "metric": "retrieved queries/sec at c=8,l=256 (sum-of-max, hybrid)" if (C, L) == (8, 256)
+                  else f"retrieved queries/sec at c={C},l={L} ({', '.join(rules)})",
+        "value": value, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8 activity in/out, 1-bit packed W and state, u32 bitwise/integer arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: C={C} L={L} n={n} M={w.M} K={K} erased={w.e} cap={w.max_iters} "
+                               f"rules={'+'.join(rules)} (one step = one gbnn_retrieve per rule over the batch)",
+                   "queries_per_step": queries_per_step, "seed": w.seed, "density": w.density(),
+                   "kernel_path": gb.gbnn_retrieve_path(C, L, rules[0], V0d, outs[rules[0]])},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": f"gbnn_retrieve[{dominant}]",
+                     "algorithmic_bytes_per_launch": abytes},
+        "cpu_baseline": cpu,
+        "per_rule": per_rule,
+        "store": {"messages": w.M, "seconds_incl_launch_and_sync": store_s},
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
