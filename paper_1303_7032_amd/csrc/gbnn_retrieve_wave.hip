@@ -6,9 +6,9 @@
 // one slot ("group"), and 64/LW clusters share a slot.  A row of W (or of the cluster-summary
 // table) in the canonical layout is then one coalesced 256-byte load per slot.
 //
-// All three rules are built on one primitive: walk the currently active neurons j with scalar
-// code (ballot -> readlane -> count-trailing-zeros) and fetch row j of W, which by symmetry of W
-// (Section IV-B) holds, for every neuron i at once, whether j signals i.
+// All three rules are built on one primitive: list the currently active neurons j and fetch
+// row j of W, which by symmetry of W (Section IV-B) holds, for every neuron i at once, whether j
+// signals i.
 //   sum-of-max (Eq. 6-7 / bail-out-early, Section IV-D): neuron i stays on iff it is on and, for
 //     every other cluster c', the OR of the rows of the active neurons of c' has bit i.  Because
 //     dead neurons stay dead (Lemma 1) a cluster whose active set did not change in the previous
@@ -16,20 +16,35 @@
 //   sum-of-sum (Eq. 3-5): the rows are added into bit-sliced counters (one register per binary
 //     digit of the score), gamma is added to active neurons, and the per-cluster maximum is
 //     found digit by digit from the top with a ballot per digit.
-//   hybrid (Algorithm 2): pass 1 is the counter form restricted to "== C - e"; later passes are
-//     the sum-of-max update applied to the lanes of erased clusters only.
+//   hybrid (Algorithm 2): pass 1 keeps the erased-cluster neurons with exactly C - e signals: the
+//     AND of the known neurons' rows when each known cluster holds one active neuron, the counter
+//     form otherwise; later passes are the sum-of-max update applied to erased clusters only.
+//
+// The kernel is bound by instruction issue, not by memory latency, so the listing of active
+// neurons is done with vector code: every lane ranks its own set bits with ballot + mbcnt and
+// pushes their neuron indices to lane `rank` with ds_permute; the row loop then needs one
+// v_readlane and one buffer_load (row offset in the scalar-offset operand) per row.
+#include <cstdlib>
+
 #include "gbnn_internal.h"
 
 namespace gbnn {
 namespace {
 
-constexpr int kPlanes = 16;  // binary digits of a score: n + gamma < 2^16 by the interface limits
+constexpr int kPlanes = 16;   // binary digits of a score: n + gamma < 2^16 by the interface limits
+constexpr int kInFlight = 4;  // row loads issued before the first is consumed
+constexpr int kListMax = 63;  // entries of the in-register row list (lane 63 takes the idle pushes)
 
 __device__ __forceinline__ uint32_t readlane(uint32_t x, int l)
 {
     return (uint32_t)__builtin_amdgcn_readlane((int)x, l);
 }
 __device__ __forceinline__ uint64_t ballot(bool p) { return (uint64_t)__ballot(p); }
+// Number of set bits of the wave-uniform mask m in lanes below this one.
+__device__ __forceinline__ uint32_t mbcnt(uint64_t m)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
 
 // 4 activity bytes (0/1 in bit 0) -> 4 bits, byte k -> bit k.  The multiplier places byte k's
 // bit at 21+k without carries.
@@ -47,39 +62,27 @@ __device__ __forceinline__ uint4 spread16(uint32_t h)
 
 template <int NW>
 struct Ctx {
-    const uint32_t *W;
-    const uint32_t *has;
+    __amdgpu_buffer_rsrc_t wrsrc;    // W as a raw buffer: loads beyond its end return 0
+    __amdgpu_buffer_rsrc_t hasrsrc;  // the cluster-summary table
     int nw, C;
-    int lane, log2lw, cps, grp, grpstart;
+    uint32_t rowbytes;               // nw * 4
+    int lane, log2lw, log2L, cps, grp, grpstart;
     uint64_t grpmask;        // low LW bits set
     bool valid[NW];          // this lane's word of slot t exists
+    uint32_t woffb[NW];      // byte offset of this lane's word of slot t in a row; 0 if it does not exist
+    uint32_t myc[NW];        // cluster of this lane's word of slot t (never matched if it does not exist)
     uint64_t validmask[NW];  // ballot of valid
     uint64_t lead[NW];       // first lane of every existing group of slot t
 };
 
+// Row at byte offset `rowoff` (wave-uniform) of a table.  Lanes without a word read word 0 of the
+// row: in bounds, and what they compute is never stored.
 template <int NW>
-__device__ __forceinline__ void load_row(const Ctx<NW> &x, const uint32_t *base, int64_t j, uint32_t (&r)[NW])
+__device__ __forceinline__ void load_row(const Ctx<NW> &x, __amdgpu_buffer_rsrc_t rsrc, uint32_t rowoff,
+                                         uint32_t (&r)[NW])
 {
-    const uint32_t *row = base + j * x.nw;
 #pragma unroll
-    for (int u = 0; u < NW; ++u) r[u] = x.valid[u] ? row[u * 64 + x.lane] : 0u;
-}
-
-// f(j) for every active neuron j held in slot t by the lanes of `lanes` (wave-uniform), ascending.
-template <class F>
-__device__ __forceinline__ void for_each_active(uint32_t vt, uint64_t lanes, int t, F &&f)
-{
-    while (lanes) {
-        const int sl = __builtin_ctzll(lanes);
-        lanes &= lanes - 1;
-        uint32_t word = readlane(vt, sl);
-        const int jb = ((t << 6) + sl) << 5;
-        while (word) {
-            const int b = __builtin_ctz(word);
-            word &= word - 1;
-            f(jb + b);
-        }
-    }
+    for (int u = 0; u < NW; ++u) r[u] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, x.woffb[u], rowoff, 0);
 }
 
 // True in every lane whose group has a set bit in the wave-uniform lane mask m.
@@ -89,42 +92,192 @@ __device__ __forceinline__ bool group_any(const Ctx<NW> &x, uint64_t m)
     return ((m >> x.grpstart) & x.grpmask) != 0;
 }
 
+// Lane-mask helpers for groups (a group = the LW consecutive lanes holding one cluster).
+// fold_or / fold_and leave, on the first lane of every group, the OR / AND of the group's bits.
+template <int NW>
+__device__ __forceinline__ uint64_t fold_or(const Ctx<NW> &x, uint64_t m)
+{
+    for (int sh = 1; sh < (1 << x.log2lw); sh <<= 1) m |= m >> sh;
+    return m;
+}
+template <int NW>
+__device__ __forceinline__ uint64_t fold_and(const Ctx<NW> &x, uint64_t m)
+{
+    for (int sh = 1; sh < (1 << x.log2lw); sh <<= 1) m &= m >> sh;
+    return m;
+}
+
+// acc &= (R | own-cluster mask of c); R = 0.
+template <int NW>
+__device__ __forceinline__ void and_cluster(const Ctx<NW> &x, uint32_t c, uint32_t (&R)[NW], uint32_t (&acc)[NW])
+{
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+        acc[u] &= (x.myc[u] == c) ? 0xFFFFFFFFu : R[u];
+        R[u] = 0u;
+    }
+}
+
+// Lists the set bits of pw[] (ascending neuron index) in a register: lane i of `list` gets
+// (neuron index + 1) of the i-th set bit, lanes past the end get 0.  Returns the number of
+// entries, or -1 if there are more than kListMax (list is then unusable).
+template <int NW>
+__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], uint32_t &list)
+{
+    int base = 0;
+    list = 0u;
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        const uint32_t pc = __popc(pw[t]);
+        uint64_t mk = ballot(pc > 0u);
+        if (!mk) continue;
+        // rank of this lane's first bit = bits in lower lanes = sum over k of #(lower lanes with > k bits)
+        uint32_t rank = (uint32_t)base;
+        int tot = 0;
+        for (uint32_t k = 1; mk; ++k) {
+            rank += mbcnt(mk);
+            tot += __builtin_popcountll(mk);
+            mk = ballot(pc > k);
+        }
+        base += tot;
+        if (base > kListMax) return -1;
+        uint32_t w = pw[t];
+        do {
+            const bool has = (w != 0u);
+            const uint32_t j = ((uint32_t)((t << 6) + x.lane) << 5) + (uint32_t)__builtin_ctz(w | 0x80000000u);
+            // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
+            list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
+            w &= w - 1u;
+            ++rank;
+        } while (ballot(w != 0u));
+    }
+    return base;
+}
+
+// acc &= , for every cluster c' with entries in the list, (OR of the rows of its entries | own mask).
+// Entries of one cluster are adjacent (the list is sorted by neuron index).
+template <int NW>
+__device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int total, uint32_t (&acc)[NW])
+{
+    const uint32_t jv = list - 1u;
+    const uint32_t offv = jv * x.rowbytes;
+    const uint32_t cv = jv >> x.log2L;
+    const uint32_t prev = (uint32_t)__shfl_up((int)cv, 1);
+    const uint64_t first = ballot(x.lane == 0 || cv != prev);  // entry starts a new cluster
+    uint32_t R[NW];
+#pragma unroll
+    for (int u = 0; u < NW; ++u) R[u] = 0u;
+    int curc = -1;
+    for (int i0 = 0; i0 < total; i0 += kInFlight) {
+        uint32_t r[kInFlight][NW];
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) {
+            const int idx = (i0 + q < total) ? i0 + q : total - 1;  // past the end: re-read the last row
+            load_row(x, x.wrsrc, readlane(offv, idx), r[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) {
+            const int i = i0 + q;
+            if (i >= total) break;
+            if ((first >> i) & 1ull) {
+                if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+                curc = (int)readlane(cv, i);
+            }
+#pragma unroll
+            for (int u = 0; u < NW; ++u) R[u] |= r[q][u];
+        }
+    }
+    if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+}
+
+// The same, with scalar enumeration and one row in flight: for more rows than the list holds.
+template <int NW>
+__device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32_t (&pw)[NW], uint32_t (&acc)[NW])
+{
+    uint32_t R[NW];
+#pragma unroll
+    for (int u = 0; u < NW; ++u) R[u] = 0u;
+    int curc = -1;
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        uint64_t lanes = ballot(pw[t] != 0u);
+        while (lanes) {
+            const int sl = __builtin_ctzll(lanes);
+            lanes &= lanes - 1;
+            uint32_t word = readlane(pw[t], sl);
+            const int c = (t << 6 | sl) >> x.log2lw;
+            if (c != curc) {
+                if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+                curc = c;
+            }
+            while (word) {
+                const uint32_t j = ((uint32_t)(t << 6 | sl) << 5) + (uint32_t)__builtin_ctz(word);
+                word &= word - 1;
+                uint32_t r[NW];
+                load_row(x, x.wrsrc, j * x.rowbytes, r);
+#pragma unroll
+                for (int u = 0; u < NW; ++u) R[u] |= r[u];
+            }
+        }
+    }
+    if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+}
+
 // One sum-of-max pass over the dirty clusters: acc = v AND, for each dirty cluster c',
 // (OR of rows of active neurons of c'  |  own-cluster mask of c').
 template <int NW>
 __device__ __forceinline__ void som_pass(const Ctx<NW> &x, const uint32_t (&v)[NW], const uint64_t (&dirty)[NW],
                                          uint32_t (&acc)[NW])
 {
-#pragma unroll
-    for (int t = 0; t < NW; ++t) acc[t] = v[t];
+    uint32_t pw[NW];  // words that list rows to fetch: active words of dirty, not fully active clusters
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
+        acc[t] = v[t];
+        pw[t] = 0u;
+    }
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        if (dirty[t] == 0) continue;
         const uint64_t full = ballot(v[t] == 0xFFFFFFFFu);
         const uint64_t nz = ballot(v[t] != 0u);
-        uint64_t m = dirty[t];
-        while (m) {
-            const int g = __builtin_ctzll(m) >> x.log2lw;
-            const uint64_t gl = x.grpmask << (g << x.log2lw);
-            m &= ~gl;
-            uint32_t R[NW];
+        const uint64_t dleads = fold_or(x, dirty[t]) & x.lead[t];  // first lanes of the dirty groups
+        uint64_t sum_leads = full ? (fold_and(x, full) & dleads) : 0;  // ... that are fully active
+        uint64_t empty_leads = dleads & ~fold_or(x, nz);              // ... that hold no active neuron
+        // Fully active cluster (an erased cluster at the start of sum-of-max, Section III-C): its
+        // contribution is its stored summary row.
+        uint64_t fullgroups = 0;
+        while (sum_leads) {
+            uint32_t r[kInFlight][NW];
+            int c[kInFlight];
+            uint64_t sl = sum_leads;
 #pragma unroll
-            for (int u = 0; u < NW; ++u) R[u] = 0u;
-            if ((full & gl) == gl) {
-                // every neuron of the cluster is on: its contribution is the stored summary row
-                load_row(x, x.has, (int64_t)(t * x.cps + g), R);
-            } else {
-                for_each_active(v[t], nz & gl, t, [&](int j) {
-                    uint32_t r[NW];
-                    load_row(x, x.W, (int64_t)j, r);
-#pragma unroll
-                    for (int u = 0; u < NW; ++u) R[u] |= r[u];
-                });
+            for (int q = 0; q < kInFlight; ++q) {
+                const int lead = __builtin_ctzll(sl);
+                if (sl & (sl - 1)) sl &= sl - 1;  // keep the last one for the idle slots
+                c[q] = t * x.cps + (lead >> x.log2lw);
+                load_row(x, x.hasrsrc, (uint32_t)c[q] * x.rowbytes, r[q]);
             }
-            const bool own = (x.grp == g);
 #pragma unroll
-            for (int u = 0; u < NW; ++u) acc[u] &= (u == t && own) ? 0xFFFFFFFFu : R[u];
+            for (int q = 0; q < kInFlight; ++q) {
+                if (!sum_leads) break;
+                fullgroups |= x.grpmask << __builtin_ctzll(sum_leads);
+                sum_leads &= sum_leads - 1;
+                and_cluster(x, (uint32_t)c[q], r[q], acc);
+            }
         }
+        // A dirty cluster with no active neuron signals nobody: everything outside it goes off.
+        for (; empty_leads; empty_leads &= empty_leads - 1) {
+            uint32_t zero[NW];
+#pragma unroll
+            for (int u = 0; u < NW; ++u) zero[u] = 0u;
+            and_cluster(x, (uint32_t)(t * x.cps + (__builtin_ctzll(empty_leads) >> x.log2lw)), zero, acc);
+        }
+        if (group_any(x, dirty[t]) && !group_any(x, fullgroups)) pw[t] = v[t];
     }
+    uint32_t list;
+    const int total = build_list(x, pw, list);
+    if (total > 0) apply_rows(x, list, total, acc);
+    else if (total < 0) apply_rows_serial(x, pw, acc);
 }
 
 // Bit-sliced sum over the rows of all active neurons: pl[p] holds digit p of
@@ -139,23 +292,30 @@ __device__ __forceinline__ int count_signals(const Ctx<NW> &x, const uint32_t (&
     int rows = 0;
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
-        const uint64_t nz = ballot(v[t] != 0u);
-        for_each_active(v[t], nz, t, [&](int j) {
-            uint32_t carry[NW];
-            load_row(x, x.W, (int64_t)j, carry);
-            ++rows;
-            const int np = 32 - __builtin_clz((unsigned)rows);  // digits a count of `rows` can need
+        uint64_t lanes = ballot(v[t] != 0u);
+        while (lanes) {
+            const int sl = __builtin_ctzll(lanes);
+            lanes &= lanes - 1;
+            uint32_t word = readlane(v[t], sl);
+            while (word) {
+                const uint32_t j = ((uint32_t)(t << 6 | sl) << 5) + (uint32_t)__builtin_ctz(word);
+                word &= word - 1;
+                uint32_t carry[NW];
+                load_row(x, x.wrsrc, j * x.rowbytes, carry);
+                ++rows;
+                const int np = 32 - __builtin_clz((unsigned)rows);  // digits a count of `rows` can need
 #pragma unroll
-            for (int p = 0; p < kPlanes; ++p) {
-                if (p >= np) break;
+                for (int p = 0; p < kPlanes; ++p) {
+                    if (p >= np) break;
 #pragma unroll
-                for (int u = 0; u < NW; ++u) {
-                    const uint32_t c2 = pl[p][u] & carry[u];
-                    pl[p][u] ^= carry[u];
-                    carry[u] = c2;
+                    for (int u = 0; u < NW; ++u) {
+                        const uint32_t c2 = pl[p][u] & carry[u];
+                        pl[p][u] ^= carry[u];
+                        carry[u] = c2;
+                    }
                 }
             }
-        });
+        }
     }
     return rows;
 }
@@ -176,12 +336,16 @@ template <int NW, int RULE>
 __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2lw)
 {
     Ctx<NW> x;
-    x.W = a.W;
-    x.has = a.has;
     x.nw = a.nw;
     x.C = a.C;
+    x.rowbytes = (uint32_t)a.nw * 4u;
+    x.wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.W), 0, (int)((uint32_t)a.n * x.rowbytes),
+                                                0x00020000);
+    x.hasrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.has), 0,
+                                                  (int)((uint32_t)a.C * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
     x.log2lw = log2lw;
+    x.log2L = log2lw + 5;
     x.cps = 64 >> log2lw;
     x.grp = x.lane >> log2lw;
     x.grpstart = x.grp << log2lw;
@@ -189,6 +353,8 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
         x.valid[t] = (t * 64 + x.lane) < a.nw;
+        x.woffb[t] = x.valid[t] ? (uint32_t)(t * 64 + x.lane) * 4u : 0u;
+        x.myc[t] = x.valid[t] ? (uint32_t)(t * x.cps + x.grp) : 0xFFFFu;
         x.validmask[t] = ballot(x.valid[t]);
         x.lead[t] = ballot(x.valid[t] && (x.lane == x.grpstart));
     }
@@ -198,15 +364,13 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
     for (int64_t k = wave; k < a.K; k += nwaves) {
         // ---- probe load: 32 bytes per word, packed to bits
         uint32_t v[NW];
-        const uint4 *src = reinterpret_cast<const uint4 *>(a.V0 + k * a.n);
+        const uint8_t *src = a.V0 + k * a.n;
 #pragma unroll
         for (int t = 0; t < NW; ++t) {
-            v[t] = 0u;
-            if (x.valid[t]) {
-                const uint4 lo = src[(t * 64 + x.lane) * 2];
-                const uint4 hi = src[(t * 64 + x.lane) * 2 + 1];
-                v[t] = pack16(lo) | (pack16(hi) << 16);
-            }
+            const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
+            const uint4 lo = p[0];
+            const uint4 hi = p[1];
+            v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
         }
 
         int it = 0;
@@ -234,40 +398,57 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
             // Algorithm 2.  Erased clusters = clusters with no active neuron in the probe.
             bool erased[NW];
             uint64_t erasedmask[NW];
-            int known = 0;
+            uint64_t dirty[NW];
+            int known = 0, nzlanes = 0;
+            bool onehot = true;
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
                 const uint64_t nz = ballot(v[t] != 0u);
+                const uint64_t single = ballot(v[t] != 0u && (v[t] & (v[t] - 1u)) == 0u);
+                onehot = onehot && (single == nz);
+                nzlanes += __builtin_popcountll(nz);
                 erased[t] = x.valid[t] && !group_any(x, nz);
                 erasedmask[t] = ballot(erased[t]);
-                uint64_t y = nz;
-                for (int sh = 1; sh < (1 << log2lw); sh <<= 1) y |= y >> sh;  // group OR lands on its first lane
-                known += __builtin_popcountll(y & x.lead[t]);
+                known += __builtin_popcountll(fold_or(x, nz) & x.lead[t]);
             }
-            const int target = known;  // C - e
-            // lines 2-5: keep the neurons of erased clusters that receive exactly C - e signals
-            uint32_t pl[kPlanes][NW];
-            const int rows = count_signals(x, v, pl);
-            const int np = rows ? 32 - __builtin_clz((unsigned)rows) : 0;
+            if (onehot && nzlanes == known) {
+                // Every known cluster holds exactly one active neuron (the probe contract).  Then
+                // "exactly C - e signals" (lines 2-5) means "adjacent to every known active neuron":
+                // the AND of their rows, which is a sum-of-max pass over the known clusters applied
+                // to fully active erased clusters.
+                uint32_t vi[NW], acc[NW];
 #pragma unroll
-            for (int u = 0; u < NW; ++u) {
-                uint32_t eq = 0xFFFFFFFFu;
-#pragma unroll
-                for (int p = 0; p < kPlanes; ++p) {
-                    if (p >= np) break;
-                    eq &= ((target >> p) & 1) ? pl[p][u] : ~pl[p][u];
+                for (int t = 0; t < NW; ++t) {
+                    vi[t] = erased[t] ? 0xFFFFFFFFu : v[t];
+                    dirty[t] = x.validmask[t] & ~erasedmask[t];
                 }
-                if (erased[u]) v[u] = eq;
+                som_pass(x, vi, dirty, acc);
+#pragma unroll
+                for (int t = 0; t < NW; ++t) {
+                    if (erased[t]) v[t] = acc[t];
+                    dirty[t] = erasedmask[t];  // known clusters have just been applied: clean
+                }
+            } else {
+                // General probe: count the signals with bit-sliced counters, keep "== C - e".
+                uint32_t pl[kPlanes][NW];
+                const int rows = count_signals(x, v, pl);
+                const int np = rows ? 32 - __builtin_clz((unsigned)rows) : 0;
+#pragma unroll
+                for (int u = 0; u < NW; ++u) {
+                    uint32_t eq = 0xFFFFFFFFu;
+#pragma unroll
+                    for (int p = 0; p < kPlanes; ++p) {
+                        if (p >= np) break;
+                        eq &= ((known >> p) & 1) ? pl[p][u] : ~pl[p][u];
+                    }
+                    if (erased[u]) v[u] = eq;
+                    dirty[u] = x.validmask[u];
+                }
             }
             int p = 1;
             if (p == a.max_iters) {
                 it = -p;
             } else {
-                // When every known cluster holds exactly one active neuron, "exactly C - e signals"
-                // already means "adjacent to every known active neuron": known clusters are clean.
-                uint64_t dirty[NW];
-#pragma unroll
-                for (int t = 0; t < NW; ++t) dirty[t] = (rows == known) ? erasedmask[t] : x.validmask[t];
                 for (;;) {
                     uint32_t acc[NW];
                     som_pass(x, v, dirty, acc);
@@ -330,12 +511,13 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
 
         // ---- result store
         if (a.iters && x.lane == 0) a.iters[k] = it;
-        uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + k * a.n);
+        uint8_t *dstb = a.Vout + k * a.n;
 #pragma unroll
         for (int t = 0; t < NW; ++t) {
             if (x.valid[t]) {
-                dst[(t * 64 + x.lane) * 2] = spread16(v[t] & 0xFFFFu);
-                dst[(t * 64 + x.lane) * 2 + 1] = spread16(v[t] >> 16);
+                uint4 *dst = reinterpret_cast<uint4 *>(dstb + x.woffb[t] * 8u);
+                dst[0] = spread16(v[t] & 0xFFFFu);
+                dst[1] = spread16(v[t] >> 16);
             }
         }
     }
@@ -345,7 +527,11 @@ template <int NW>
 hipError_t launch_nw(const RetrieveArgs &a, int log2lw, hipStream_t s)
 {
     int64_t blocks = (a.K + 3) / 4;
-    const int64_t cap = 256 * 8;  // 256 CUs x 8 workgroups of 4 waves = every wave slot of the chip
+    int64_t cap = 256 * 8;  // 256 CUs x 8 workgroups of 4 waves = every wave slot of the chip
+    if (const char *e = std::getenv("GBNN_GRID_BLOCKS")) {  // tuning aid
+        const long v = std::atol(e);
+        if (v > 0) cap = v;
+    }
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(256);
     switch (a.rule) {
