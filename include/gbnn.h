@@ -59,8 +59,9 @@ typedef enum {
 size_t gbnn_w_row_words(int C, int L);
 /* Bytes of W: n * gbnn_w_row_words * 4.  0 if the shape is outside the limits. */
 size_t gbnn_w_bytes(int C, int L);
-/* Bytes of scratch device memory gbnn_retrieve needs for this shape, batch and rule (a
- * multiple of 256, never 0 for a valid shape).  0 if an argument is outside the limits. */
+/* Bytes of the device workspace that gbnn_prepare fills and gbnn_retrieve reads for this shape,
+ * batch and rule (a multiple of 256, never 0 for a valid shape; about the size of W).  0 if an
+ * argument is outside the limits. */
 size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule);
 
 /*
@@ -74,6 +75,19 @@ size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule);
  *          [0,L); such a message is skipped entirely.  Zero it before the call.
  */
 int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream);
+
+/*
+ * Derives from W the read-only tables the retrieval kernels use and writes them to `workspace`:
+ * a copy of W whose intra-cluster blocks are all ones (so that "OR of the rows of the active
+ * neurons of cluster c', or the neuron is itself in c'" -- the bail-out-early test of Section
+ * IV-D -- is a plain OR of rows), and one summary row per cluster, the OR of its L rows (what a
+ * fully active cluster, i.e. an erased cluster at the start of sum-of-max, contributes).
+ * Call it after W changes (gbnn_store) and before gbnn_retrieve; the workspace then serves any
+ * number of gbnn_retrieve calls on that W, of any rule and batch size up to the K it was sized
+ * for.  It depends only on W, C and L.
+ *   workspace  device, 256-byte aligned, at least gbnn_workspace_bytes(C, L, K, rule) bytes.
+ */
+int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Retrieval of K probes, each independently, iterated until its activity vector is reproduced
@@ -94,9 +108,8 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
  *   iters_out  device int32_t[K] or NULL: +p if pass p reproduced its input (the confirming
  *          pass counts; for the hybrid the test is made from pass 2 on), -max_iters if the cap
  *          was reached first.
- *   workspace  device scratch, 256-byte aligned, at least gbnn_workspace_bytes(...) bytes;
- *          contents are undefined before and after the call.  Two calls that overlap in time
- *          must not share it.
+ *   workspace  the workspace filled by gbnn_prepare for this W; only read here, so calls that
+ *          overlap in time may share it.
  */
 int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,

@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_workspace_bytes.argtypes = [ci, ci, i64, ci]
         L.gbnn_store.restype = ci
         L.gbnn_store.argtypes = [vp, ci, ci, vp, i64, vp, vp]
+        L.gbnn_prepare.restype = ci
+        L.gbnn_prepare.argtypes = [vp, ci, ci, vp, sz, vp]
         L.gbnn_retrieve.restype = ci
         L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
         L.gbnn_strerror.restype = ctypes.c_char_p
@@ -111,13 +113,27 @@ def gbnn_store(W: torch.Tensor, C: int, L: int, msgs: torch.Tensor, status: torc
     _check(lib().gbnn_store(W.data_ptr(), C, L, msgs.data_ptr() if M else 0, M, st, _stream(W)))
 
 
+def gbnn_prepare(W: torch.Tensor, C: int, L: int, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Fill (and, if not supplied, allocate) the workspace gbnn_retrieve reads: derived tables of W.
+    Call again whenever W changes.  Returns the workspace (a uint8 tensor on W's device)."""
+    _dev(W, torch.int32, "W")
+    if W.numel() * 4 != gbnn_w_bytes(C, L):
+        _check(ERRORS["SHAPE"])
+    if workspace is None:
+        workspace = torch.empty(gbnn_workspace_bytes(C, L, 0, SUM_OF_MAX), dtype=torch.uint8, device=W.device)
+    _dev(workspace, torch.uint8, "workspace")
+    _check(lib().gbnn_prepare(W.data_ptr(), C, L, workspace.data_ptr(), workspace.numel(), _stream(W)))
+    return workspace
+
+
 def gbnn_retrieve(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma: int = 1, max_iters: int = 20,
                   V_out: torch.Tensor | None = None, iters_out: torch.Tensor | None = None,
                   workspace: torch.Tensor | None = None, want_iters: bool = True):
     """Retrieve the K probes of V0 (uint8[K][n]).  Returns (V_out, iters_out).
 
-    Output tensors and the workspace are allocated with torch when not supplied (pass them
-    in to keep allocation out of a timed loop).  Work is enqueued on the current stream.
+    `workspace` is what gbnn_prepare returned for this W; if it is None it is built here (one
+    more pass over W per call: pass it in when retrieving repeatedly).  Output tensors are
+    allocated with torch when not supplied.  Work is enqueued on the current stream.
     """
     r = _rule(rule)
     _dev(W, torch.int32, "W")
@@ -137,9 +153,8 @@ def gbnn_retrieve(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma
         _dev(iters_out, torch.int32, "iters_out")
         if iters_out.numel() != K:
             _check(ERRORS["SHAPE"])
-    need = gbnn_workspace_bytes(C, L, K, r)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=V0.device)
+        workspace = gbnn_prepare(W, C, L)
     _dev(workspace, torch.uint8, "workspace")
     _check(lib().gbnn_retrieve(W.data_ptr(), C, L, V0.data_ptr() if K else 0, V_out.data_ptr() if K else 0, K, r,
                                gamma, max_iters, iters_out.data_ptr() if iters_out is not None else 0,

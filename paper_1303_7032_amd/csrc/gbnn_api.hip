@@ -16,8 +16,6 @@ bool shape_ok(int C, int L)
 
 bool rule_ok(int rule) { return rule == GBNN_SUM_OF_SUM || rule == GBNN_SUM_OF_MAX || rule == GBNN_HYBRID; }
 
-size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Words per lane of the one-wave-per-probe kernel, or 0 for the any-shape kernel.
@@ -48,7 +46,7 @@ size_t gbnn_w_bytes(int C, int L)
 size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule)
 {
     if (!shape_ok(C, L) || K < 0 || !rule_ok(rule)) return 0;
-    return round256(workspace_has_bytes(C, (int)gbnn_w_row_words(C, L))) + 256;
+    return workspace_total_bytes(C, L, (int)gbnn_w_row_words(C, L));
 }
 
 int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream)
@@ -57,6 +55,20 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
     if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
     const hipError_t e =
         launch_store(W, C, L, (int)gbnn_w_row_words(C, L), msgs, M, status, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!shape_ok(C, L)) return GBNN_ERR_SHAPE;
+    if (!W) return GBNN_ERR_NULL;
+    const int nw = (int)gbnn_w_row_words(C, L);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, nw))
+        return GBNN_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    const hipError_t e =
+        launch_prepare(W, C, L, nw, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
+                       reinterpret_cast<uint32_t *>(ws), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
@@ -76,7 +88,9 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
     hipStream_t s = static_cast<hipStream_t>(stream);
     RetrieveArgs a;
     a.W = W;
-    a.has = static_cast<const uint32_t *>(workspace);
+    a.nw = (int)gbnn_w_row_words(C, L);
+    a.Wb = static_cast<const uint32_t *>(workspace);
+    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
     a.V0 = V0;
     a.Vout = V_out;
     a.iters = iters_out;
@@ -84,18 +98,12 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
     a.C = C;
     a.L = L;
     a.n = C * L;
-    a.nw = (int)gbnn_w_row_words(C, L);
     a.rule = rule;
     a.gamma = gamma;
     a.max_iters = max_iters;
 
-    // The summary rows are what a fully active cluster contributes (sum-of-max initialisation);
-    // the other two rules never see a fully active cluster through it unless L is tiny, but the
-    // kernels consult the table whenever a cluster is full, so it is always built.
-    hipError_t e = launch_cluster_summary(W, C, L, a.nw, static_cast<uint32_t *>(workspace), s);
-    if (e != hipSuccess) return GBNN_ERR_DEVICE;
     const int wpl = pick_path(C, L, V0, V_out);
-    e = wpl ? launch_retrieve_wave(a, wpl, s) : launch_retrieve_generic(a, s);
+    const hipError_t e = wpl ? launch_retrieve_wave(a, wpl, s) : launch_retrieve_generic(a, s);
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 

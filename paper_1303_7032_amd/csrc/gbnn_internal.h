@@ -13,7 +13,8 @@ namespace gbnn {
 // Arguments of one retrieval launch; all pointers are device pointers.
 struct RetrieveArgs {
     const uint32_t *W;    // canonical adjacency, uint32[n][nw]
-    const uint32_t *has;  // cluster summaries, uint32[C][nw]: bit i of row c' = "some neuron of c' is adjacent to i"
+    const uint32_t *Wb;   // W with all-one intra-cluster blocks, uint32[n][nw], followed directly by
+    const uint32_t *has;  // the cluster summaries, uint32[C][nw]: bit i of row c' = "i is in c' or adjacent to a neuron of c'"
     const uint8_t *V0;    // uint8[K][n]
     uint8_t *Vout;        // uint8[K][n]
     int32_t *iters;       // int32[K] or nullptr
@@ -22,15 +23,20 @@ struct RetrieveArgs {
     int rule, gamma, max_iters;
 };
 
-// Byte offset / size of the cluster-summary table inside the caller's workspace.
-inline size_t workspace_has_bytes(int C, int nw) { return (size_t)C * (size_t)nw * sizeof(uint32_t); }
+// Workspace layout: one table of n + C rows of nw words.  Rows 0..n-1: W with all-one intra-cluster
+// blocks; rows n..n+C-1: the cluster summaries.  (One table, so that one buffer resource reaches both.)
+inline size_t workspace_has_offset(int C, int L, int nw) { return (size_t)C * L * nw * sizeof(uint32_t); }
+inline size_t workspace_total_bytes(int C, int L, int nw)
+{
+    return (((size_t)C * L + C) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
+}
 
 // Which kernel family serves a shape: 0 = generic, otherwise packed words per lane (1, 2, 4).
 int wave_words_per_lane(int C, int L);
 
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
                         hipStream_t s);
-hipError_t launch_cluster_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has, hipStream_t s);
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, hipStream_t s);
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);
 hipError_t launch_retrieve_generic(const RetrieveArgs &a, hipStream_t s);
 

@@ -63,9 +63,11 @@ __device__ __forceinline__ uint4 spread16(uint32_t h)
 template <int NW>
 struct Ctx {
     __amdgpu_buffer_rsrc_t wrsrc;    // W as a raw buffer: loads beyond its end return 0
-    __amdgpu_buffer_rsrc_t hasrsrc;  // the cluster-summary table
+    __amdgpu_buffer_rsrc_t wbrsrc;   // rows 0..n-1: W with all-one intra-cluster blocks; rows n..n+C-1: the
+                                     // cluster summaries (own-cluster bits included)
     int nw, C;
     uint32_t rowbytes;               // nw * 4
+    uint32_t nrows;                  // n
     int lane, log2lw, log2L, cps, grp, grpstart;
     uint64_t grpmask;        // low LW bits set
     bool valid[NW];          // this lane's word of slot t exists
@@ -107,22 +109,14 @@ __device__ __forceinline__ uint64_t fold_and(const Ctx<NW> &x, uint64_t m)
     return m;
 }
 
-// acc &= (R | own-cluster mask of c); R = 0.
+// Lists the rows a pass must fetch in a register: lane i of `list` gets (row index + 1) of the
+// i-th entry, lanes past the end get 0.  Entries are, slot by slot, the set bits of pw[] (row =
+// neuron index, ascending) followed by one summary row (row n + c) for every lane flagged in
+// sumlane[] (the first lane of a fully active cluster c).  Returns the number of entries, or -1
+// if there are more than kListMax (list is then unusable).
 template <int NW>
-__device__ __forceinline__ void and_cluster(const Ctx<NW> &x, uint32_t c, uint32_t (&R)[NW], uint32_t (&acc)[NW])
-{
-#pragma unroll
-    for (int u = 0; u < NW; ++u) {
-        acc[u] &= (x.myc[u] == c) ? 0xFFFFFFFFu : R[u];
-        R[u] = 0u;
-    }
-}
-
-// Lists the set bits of pw[] (ascending neuron index) in a register: lane i of `list` gets
-// (neuron index + 1) of the i-th set bit, lanes past the end get 0.  Returns the number of
-// entries, or -1 if there are more than kListMax (list is then unusable).
-template <int NW>
-__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], uint32_t &list)
+__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], const bool (&sumlane)[NW],
+                                          uint32_t &list)
 {
     int base = 0;
     list = 0u;
@@ -130,73 +124,98 @@ __device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)
     for (int t = 0; t < NW; ++t) {
         const uint32_t pc = __popc(pw[t]);
         uint64_t mk = ballot(pc > 0u);
-        if (!mk) continue;
-        // rank of this lane's first bit = bits in lower lanes = sum over k of #(lower lanes with > k bits)
-        uint32_t rank = (uint32_t)base;
-        int tot = 0;
-        for (uint32_t k = 1; mk; ++k) {
-            rank += mbcnt(mk);
-            tot += __builtin_popcountll(mk);
-            mk = ballot(pc > k);
+        if (mk) {
+            // rank of this lane's first bit = bits in lower lanes = sum over k of #(lower lanes with > k bits)
+            uint32_t rank = (uint32_t)base;
+            int tot = 0;
+            for (uint32_t k = 1; mk; ++k) {
+                rank += mbcnt(mk);
+                tot += __builtin_popcountll(mk);
+                mk = ballot(pc > k);
+            }
+            base += tot;
+            if (base > kListMax) return -1;
+            uint32_t w = pw[t];
+            do {
+                const bool has = (w != 0u);
+                const uint32_t j = ((uint32_t)((t << 6) + x.lane) << 5) + (uint32_t)__builtin_ctz(w | 0x80000000u);
+                // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
+                list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
+                w &= w - 1u;
+                ++rank;
+            } while (ballot(w != 0u));
         }
-        base += tot;
-        if (base > kListMax) return -1;
-        uint32_t w = pw[t];
-        do {
-            const bool has = (w != 0u);
-            const uint32_t j = ((uint32_t)((t << 6) + x.lane) << 5) + (uint32_t)__builtin_ctz(w | 0x80000000u);
-            // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
-            list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
-            w &= w - 1u;
-            ++rank;
-        } while (ballot(w != 0u));
+        const uint64_t sm = ballot(sumlane[t]);
+        if (sm) {
+            const uint32_t rank = (uint32_t)base + mbcnt(sm);
+            base += __builtin_popcountll(sm);
+            if (base > kListMax) return -1;
+            list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((sumlane[t] ? rank : 63u) << 2),
+                                                          (int)(sumlane[t] ? x.nrows + x.myc[t] + 1u : 0u));
+        }
     }
     return base;
 }
 
-// acc &= , for every cluster c' with entries in the list, (OR of the rows of its entries | own mask).
-// Entries of one cluster are adjacent (the list is sorted by neuron index).
+// acc &= , for every cluster c' with entries in the list, the OR of the rows of its entries.
+// The rows come from the copy of W whose intra-cluster blocks are all ones, so a neuron of c'
+// itself always passes.  Entries of one cluster are adjacent (the list is sorted by neuron index).
 template <int NW>
 __device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int total, uint32_t (&acc)[NW])
 {
-    const uint32_t jv = list - 1u;
+    // Lanes past the end repeat the last entry, so the loop below can always fetch kInFlight rows.
+    const uint32_t jlast = readlane(list, total - 1) - 1u;
+    const uint32_t jv = (x.lane < total) ? list - 1u : jlast;
     const uint32_t offv = jv * x.rowbytes;
-    const uint32_t cv = jv >> x.log2L;
+    const uint32_t cv = (jv >= x.nrows) ? jv : (jv >> x.log2L);  // a summary row is a cluster of its own
     const uint32_t prev = (uint32_t)__shfl_up((int)cv, 1);
-    const uint64_t first = ballot(x.lane == 0 || cv != prev);  // entry starts a new cluster
+    const bool isfirst = (x.lane == 0) || (cv != prev);  // entry starts a new cluster
+    const uint64_t first = ballot(isfirst);
+    if (__builtin_popcountll(first) == total) {
+        // every cluster lists one row: plain AND of the rows
+        for (int i0 = 0; i0 < total; i0 += kInFlight) {
+            uint32_t r[kInFlight][NW];
+#pragma unroll
+            for (int q = 0; q < kInFlight; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+#pragma unroll
+            for (int q = 0; q < kInFlight; ++q)
+#pragma unroll
+                for (int u = 0; u < NW; ++u) acc[u] &= r[q][u];
+        }
+        return;
+    }
+    // General case, branch-free: R collects the OR of the current cluster's rows; at the first row
+    // of the next cluster (keep == 0) it is ANDed into acc and restarted.
+    const uint32_t keepv = isfirst ? 0u : 0xFFFFFFFFu;
     uint32_t R[NW];
 #pragma unroll
-    for (int u = 0; u < NW; ++u) R[u] = 0u;
-    int curc = -1;
+    for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
     for (int i0 = 0; i0 < total; i0 += kInFlight) {
         uint32_t r[kInFlight][NW];
 #pragma unroll
-        for (int q = 0; q < kInFlight; ++q) {
-            const int idx = (i0 + q < total) ? i0 + q : total - 1;  // past the end: re-read the last row
-            load_row(x, x.wrsrc, readlane(offv, idx), r[q]);
-        }
+        for (int q = 0; q < kInFlight; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
 #pragma unroll
         for (int q = 0; q < kInFlight; ++q) {
-            const int i = i0 + q;
-            if (i >= total) break;
-            if ((first >> i) & 1ull) {
-                if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
-                curc = (int)readlane(cv, i);
+            const uint32_t keep = readlane(keepv, i0 + q);
+#pragma unroll
+            for (int u = 0; u < NW; ++u) {
+                acc[u] &= R[u] | keep;
+                R[u] = (R[u] & keep) | r[q][u];
             }
-#pragma unroll
-            for (int u = 0; u < NW; ++u) R[u] |= r[q][u];
         }
     }
-    if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+#pragma unroll
+    for (int u = 0; u < NW; ++u) acc[u] &= R[u];
 }
 
 // The same, with scalar enumeration and one row in flight: for more rows than the list holds.
 template <int NW>
-__device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32_t (&pw)[NW], uint32_t (&acc)[NW])
+__device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32_t (&pw)[NW],
+                                                  const bool (&sumlane)[NW], uint32_t (&acc)[NW])
 {
     uint32_t R[NW];
 #pragma unroll
-    for (int u = 0; u < NW; ++u) R[u] = 0u;
+    for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
     int curc = -1;
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
@@ -207,20 +226,32 @@ __device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32
             uint32_t word = readlane(pw[t], sl);
             const int c = (t << 6 | sl) >> x.log2lw;
             if (c != curc) {
-                if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+#pragma unroll
+                for (int u = 0; u < NW; ++u) {
+                    acc[u] &= R[u];
+                    R[u] = 0u;
+                }
                 curc = c;
             }
             while (word) {
                 const uint32_t j = ((uint32_t)(t << 6 | sl) << 5) + (uint32_t)__builtin_ctz(word);
                 word &= word - 1;
                 uint32_t r[NW];
-                load_row(x, x.wrsrc, j * x.rowbytes, r);
+                load_row(x, x.wbrsrc, j * x.rowbytes, r);
 #pragma unroll
                 for (int u = 0; u < NW; ++u) R[u] |= r[u];
             }
         }
+        for (uint64_t sm = ballot(sumlane[t]); sm; sm &= sm - 1) {
+            const uint32_t c = (uint32_t)(t * x.cps + (__builtin_ctzll(sm) >> x.log2lw));
+            uint32_t r[NW];
+            load_row(x, x.wbrsrc, (x.nrows + c) * x.rowbytes, r);
+#pragma unroll
+            for (int u = 0; u < NW; ++u) acc[u] &= r[u];
+        }
     }
-    if (curc >= 0) and_cluster(x, (uint32_t)curc, R, acc);
+#pragma unroll
+    for (int u = 0; u < NW; ++u) acc[u] &= R[u];
 }
 
 // One sum-of-max pass over the dirty clusters: acc = v AND, for each dirty cluster c',
@@ -229,55 +260,34 @@ template <int NW>
 __device__ __forceinline__ void som_pass(const Ctx<NW> &x, const uint32_t (&v)[NW], const uint64_t (&dirty)[NW],
                                          uint32_t (&acc)[NW])
 {
-    uint32_t pw[NW];  // words that list rows to fetch: active words of dirty, not fully active clusters
+    uint32_t pw[NW];   // words that list rows to fetch: active words of dirty, not fully active clusters
+    bool sumlane[NW];  // first lane of a dirty, fully active cluster: fetch its summary row instead
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
         acc[t] = v[t];
         pw[t] = 0u;
-    }
-#pragma unroll
-    for (int t = 0; t < NW; ++t) {
+        sumlane[t] = false;
         if (dirty[t] == 0) continue;
-        const uint64_t full = ballot(v[t] == 0xFFFFFFFFu);
+        const uint64_t notfull = ballot(v[t] != 0xFFFFFFFFu);
         const uint64_t nz = ballot(v[t] != 0u);
-        const uint64_t dleads = fold_or(x, dirty[t]) & x.lead[t];  // first lanes of the dirty groups
-        uint64_t sum_leads = full ? (fold_and(x, full) & dleads) : 0;  // ... that are fully active
-        uint64_t empty_leads = dleads & ~fold_or(x, nz);              // ... that hold no active neuron
-        // Fully active cluster (an erased cluster at the start of sum-of-max, Section III-C): its
-        // contribution is its stored summary row.
-        uint64_t fullgroups = 0;
-        while (sum_leads) {
-            uint32_t r[kInFlight][NW];
-            int c[kInFlight];
-            uint64_t sl = sum_leads;
-#pragma unroll
-            for (int q = 0; q < kInFlight; ++q) {
-                const int lead = __builtin_ctzll(sl);
-                if (sl & (sl - 1)) sl &= sl - 1;  // keep the last one for the idle slots
-                c[q] = t * x.cps + (lead >> x.log2lw);
-                load_row(x, x.hasrsrc, (uint32_t)c[q] * x.rowbytes, r[q]);
-            }
-#pragma unroll
-            for (int q = 0; q < kInFlight; ++q) {
-                if (!sum_leads) break;
-                fullgroups |= x.grpmask << __builtin_ctzll(sum_leads);
-                sum_leads &= sum_leads - 1;
-                and_cluster(x, (uint32_t)c[q], r[q], acc);
-            }
-        }
+        const bool gdirty = group_any(x, dirty[t]);
+        // Fully active cluster (an erased cluster at the start of sum-of-max, Section III-C): what
+        // survives it is its stored summary row.
+        const bool gfull = !group_any(x, notfull);
+        if (gdirty && !gfull) pw[t] = v[t];
+        sumlane[t] = gdirty && gfull && x.valid[t] && (x.lane == x.grpstart);
         // A dirty cluster with no active neuron signals nobody: everything outside it goes off.
+        uint64_t empty_leads = ballot(gdirty && !group_any(x, nz) && x.valid[t] && (x.lane == x.grpstart));
         for (; empty_leads; empty_leads &= empty_leads - 1) {
-            uint32_t zero[NW];
+            const uint32_t c = (uint32_t)(t * x.cps + (__builtin_ctzll(empty_leads) >> x.log2lw));
 #pragma unroll
-            for (int u = 0; u < NW; ++u) zero[u] = 0u;
-            and_cluster(x, (uint32_t)(t * x.cps + (__builtin_ctzll(empty_leads) >> x.log2lw)), zero, acc);
+            for (int u = 0; u < NW; ++u) acc[u] &= (x.myc[u] == c) ? 0xFFFFFFFFu : 0u;
         }
-        if (group_any(x, dirty[t]) && !group_any(x, fullgroups)) pw[t] = v[t];
     }
     uint32_t list;
-    const int total = build_list(x, pw, list);
+    const int total = build_list(x, pw, sumlane, list);
     if (total > 0) apply_rows(x, list, total, acc);
-    else if (total < 0) apply_rows_serial(x, pw, acc);
+    else if (total < 0) apply_rows_serial(x, pw, sumlane, acc);
 }
 
 // Bit-sliced sum over the rows of all active neurons: pl[p] holds digit p of
@@ -341,8 +351,9 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
     x.rowbytes = (uint32_t)a.nw * 4u;
     x.wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.W), 0, (int)((uint32_t)a.n * x.rowbytes),
                                                 0x00020000);
-    x.hasrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.has), 0,
-                                                  (int)((uint32_t)a.C * x.rowbytes), 0x00020000);
+    x.nrows = (uint32_t)a.n;
+    x.wbrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
+                                                 (int)((uint32_t)(a.n + a.C) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
     x.log2lw = log2lw;
     x.log2L = log2lw + 5;

@@ -38,9 +38,20 @@ __global__ __launch_bounds__(256) void k_store(uint32_t *W, int C, int L, int nw
     }
 }
 
-// Cluster summary: has[c][w] = OR over the L rows j of cluster c of W[j][w], i.e. bit i says that
-// neuron i has at least one neighbour in cluster c.  It is what a fully active cluster (the
-// sum-of-max initialisation of an erased cluster, Section III-C) contributes in one pass.
+// Bits of word w (neurons 32w .. 32w+31) that lie in cluster c = neurons [c*L, (c+1)*L).
+__device__ __forceinline__ uint32_t own_mask(int c, int L, int w)
+{
+    int lo = c * L - 32 * w, hi = lo + L;
+    if (lo < 0) lo = 0;
+    if (hi > 32) hi = 32;
+    if (hi <= lo) return 0u;
+    const uint32_t upto_hi = (hi == 32) ? 0xFFFFFFFFu : ((1u << hi) - 1u);
+    return upto_hi & ~((1u << lo) - 1u);
+}
+
+// Cluster summary: has[c][w] = own bits of c | OR over the L rows j of cluster c of W[j][w], i.e.
+// bit i says that neuron i is in c or has at least one neighbour in c.  It is what a fully active
+// cluster (the sum-of-max initialisation of an erased cluster, Section III-C) lets survive.
 // Block = (cluster c, 64 consecutive words), 1024 threads = 16 row subsets x 64 words.
 constexpr int kSumRows = 16;
 __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_t *__restrict__ W, int C, int L,
@@ -60,7 +71,19 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
     __syncthreads();
     if (r == 0 && w < nw) {
         for (int k = 1; k < kSumRows; ++k) acc |= part[k][wl];
-        has[(int64_t)c * nw + w] = acc;
+        has[(int64_t)c * nw + w] = acc | own_mask(c, L, w);
+    }
+}
+
+// Wb = W with the intra-cluster blocks set to all ones: row j gets the bits of j's own cluster.
+__global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict__ W, int L, int nw, int64_t words,
+                                                     uint32_t *__restrict__ Wb)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < words; t += stride) {
+        const int j = (int)(t / nw);
+        const int w = (int)(t - (int64_t)j * nw);
+        Wb[t] = W[t] | own_mask(j / L, L, w);
     }
 }
 
@@ -77,10 +100,16 @@ hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, 
     return hipGetLastError();
 }
 
-hipError_t launch_cluster_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has, hipStream_t s)
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, hipStream_t s)
 {
     dim3 grid((unsigned)((nw + 63) / 64), (unsigned)C);
     hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t words = (int64_t)C * L * nw;
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_fill_blocks, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, words, Wb);
     return hipGetLastError();
 }
 

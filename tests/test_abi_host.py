@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"gbnn_store", "gbnn_retrieve", "gbnn_w_bytes", "gbnn_workspace_bytes", "gbnn_strerror"} <= set(names)
+    assert {"gbnn_store", "gbnn_prepare", "gbnn_retrieve", "gbnn_w_bytes", "gbnn_workspace_bytes", "gbnn_strerror"} <= set(names)
     for name in names:
         assert getattr(lib, name) is not None, name
 
@@ -49,7 +49,7 @@ def test_sizes(lib):
 def test_retrieve_argument_errors(lib):
     E = gb.ERRORS
     fake = 0x1000  # never dereferenced on the host; nothing is launched when an error is returned
-    ws = 1 << 20
+    ws = 1 << 24
 
     def call(W=fake, C=8, L=256, V0=fake, Vout=fake, K=4, rule=1, gamma=1, cap=20, it=0, wsp=fake * 16, wsb=ws):
         return lib.gbnn_retrieve(W, C, L, V0, Vout, K, rule, gamma, cap, it, wsp, wsb, 0)
@@ -69,6 +69,17 @@ def test_store_argument_errors(lib):
     assert lib.gbnn_store(0x1000, 4, 4, 0x1000, -1, 0, 0) == E["SHAPE"]
     assert lib.gbnn_store(0, 4, 4, 0x1000, 1, 0, 0) == E["NULL"]
     assert lib.gbnn_store(0x1000, 4, 4, 0, 1, 0, 0) == E["NULL"]
+
+
+def test_prepare_argument_errors(lib):
+    E = gb.ERRORS
+    need = gb.gbnn_workspace_bytes(8, 256, 0, "hybrid")
+    assert need >= gb.gbnn_w_bytes(8, 256) + 8 * 64 * 4 and need % 256 == 0
+    assert lib.gbnn_prepare(0x1000, 1, 4, 0x10000, 1 << 20, 0) == E["SHAPE"]
+    assert lib.gbnn_prepare(0, 8, 256, 0x10000, need, 0) == E["NULL"]
+    assert lib.gbnn_prepare(0x1000, 8, 256, 0, need, 0) == E["WORKSPACE"]
+    assert lib.gbnn_prepare(0x1000, 8, 256, 0x10010, need, 0) == E["WORKSPACE"]
+    assert lib.gbnn_prepare(0x1000, 8, 256, 0x10000, need - 1, 0) == E["WORKSPACE"]
 
 
 def test_strerror_and_path(lib):
