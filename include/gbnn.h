@@ -19,7 +19,8 @@
  *     a row are zero.  W must be symmetric with all-zero intra-cluster blocks (what gbnn_store
  *     produces); results for any other W are unspecified but memory-safe.
  *   - Activity layout: uint8_t[K][n], probe k contiguous (column k of the paper's matrix V,
- *     Section IV-B "Batch Retrieval"); each byte is 0 or 1 (only bit 0 of a byte is read).
+ *     Section IV-B "Batch Retrieval"); each byte must be 0 or 1 (any other value gives an
+ *     unspecified, memory-safe result).
  *   - Limits: 2 <= C <= GBNN_MAX_C, L >= 1, n <= GBNN_MAX_N, 0 <= gamma <= GBNN_MAX_GAMMA,
  *     max_iters >= 1, K >= 0, M >= 0.
  */

@@ -20,10 +20,11 @@
 //     AND of the known neurons' rows when each known cluster holds one active neuron, the counter
 //     form otherwise; later passes are the sum-of-max update applied to erased clusters only.
 //
-// The kernel is bound by instruction issue, not by memory latency, so the listing of active
-// neurons is done with vector code: every lane ranks its own set bits with ballot + mbcnt and
-// pushes their neuron indices to lane `rank` with ds_permute; the row loop then needs one
-// v_readlane and one buffer_load (row offset in the scalar-offset operand) per row.
+// The kernel is bound by instruction issue (scalar and vector instructions cost alike), not by
+// memory latency, so everything per pass is kept to a few vector instructions: cluster-wide flags
+// are DPP butterflies over the lanes of a group, the listing of active neurons ranks set bits with
+// ballot + mbcnt and pushes their indices to lane `rank` with ds_permute, and the row loop is one
+// v_readlane plus one buffer_load (row offset in the scalar-offset operand) per row.
 #include <cstdlib>
 
 #include "gbnn_internal.h"
@@ -32,8 +33,8 @@ namespace gbnn {
 namespace {
 
 constexpr int kPlanes = 16;   // binary digits of a score: n + gamma < 2^16 by the interface limits
-constexpr int kInFlight = 4;  // row loads issued before the first is consumed
-constexpr int kListMax = 63;  // entries of the in-register row list (lane 63 takes the idle pushes)
+constexpr int kListMax = 56;  // entries of the in-register row list (batches of 8 stay below lane 64;
+                              // lane 63 takes the idle pushes)
 
 __device__ __forceinline__ uint32_t readlane(uint32_t x, int l)
 {
@@ -46,12 +47,15 @@ __device__ __forceinline__ uint32_t mbcnt(uint64_t m)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
-// 4 activity bytes (0/1 in bit 0) -> 4 bits, byte k -> bit k.  The multiplier places byte k's
-// bit at 21+k without carries.
-__device__ __forceinline__ uint32_t pack4(uint32_t x) { return (((x & 0x01010101u) * 0x00204081u) >> 21) & 0xFu; }
+// 16 activity bytes (each 0 or 1) -> 16 bits, byte k -> bit k: byte-wise dot products with the
+// weights 1,2,4,8 / 16,32,64,128 (v_dot4_u32_u8 accumulates), two bytes of result glued together.
 __device__ __forceinline__ uint32_t pack16(uint4 a)
 {
-    return pack4(a.x) | (pack4(a.y) << 4) | (pack4(a.z) << 8) | (pack4(a.w) << 12);
+    uint32_t lo = __builtin_amdgcn_udot4(a.x, 0x08040201u, 0u, false);
+    lo = __builtin_amdgcn_udot4(a.y, 0x80402010u, lo, false);
+    uint32_t hi = __builtin_amdgcn_udot4(a.z, 0x08040201u, 0u, false);
+    hi = __builtin_amdgcn_udot4(a.w, 0x80402010u, hi, false);
+    return lo | (hi << 8);
 }
 // 4 bits -> 4 bytes of 0/1.
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
@@ -65,16 +69,15 @@ struct Ctx {
     __amdgpu_buffer_rsrc_t wrsrc;    // W as a raw buffer: loads beyond its end return 0
     __amdgpu_buffer_rsrc_t wbrsrc;   // rows 0..n-1: W with all-one intra-cluster blocks; rows n..n+C-1: the
                                      // cluster summaries (own-cluster bits included)
-    int nw, C;
     uint32_t rowbytes;               // nw * 4
     uint32_t nrows;                  // n
-    int lane, log2lw, log2L, cps, grp, grpstart;
-    uint64_t grpmask;        // low LW bits set
+    int lane;
     bool valid[NW];          // this lane's word of slot t exists
+    bool islead[NW];         // ... and is the first word of its cluster
     uint32_t woffb[NW];      // byte offset of this lane's word of slot t in a row; 0 if it does not exist
     uint32_t myc[NW];        // cluster of this lane's word of slot t (never matched if it does not exist)
+    uint32_t bit0[NW];       // neuron index of bit 0 of this lane's word of slot t
     uint64_t validmask[NW];  // ballot of valid
-    uint64_t lead[NW];       // first lane of every existing group of slot t
 };
 
 // Row at byte offset `rowoff` (wave-uniform) of a table.  Lanes without a word read word 0 of the
@@ -87,35 +90,49 @@ __device__ __forceinline__ void load_row(const Ctx<NW> &x, __amdgpu_buffer_rsrc_
     for (int u = 0; u < NW; ++u) r[u] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, x.woffb[u], rowoff, 0);
 }
 
-// True in every lane whose group has a set bit in the wave-uniform lane mask m.
-template <int NW>
-__device__ __forceinline__ bool group_any(const Ctx<NW> &x, uint64_t m)
+// A wave-uniform lane mask read as a per-lane flag (no vector arithmetic: the mask is the condition).
+__device__ __forceinline__ bool lane_of(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+// OR over the 2^LG lanes of this lane's group (a group = the lanes holding one cluster), left in
+// every lane of the group: a butterfly of DPP moves inside a row of 16 lanes, ds_bpermute beyond.
+template <int CTRL>
+__device__ __forceinline__ uint32_t or_dpp(uint32_t v)
 {
-    return ((m >> x.grpstart) & x.grpmask) != 0;
+    return v | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int LG>
+__device__ __forceinline__ uint32_t group_or(uint32_t v)
+{
+    if (LG >= 1) v = or_dpp<0xB1>(v);   // quad_perm [1,0,3,2]
+    if (LG >= 2) v = or_dpp<0x4E>(v);   // quad_perm [2,3,0,1]
+    if (LG >= 3) v = or_dpp<0x141>(v);  // row_half_mirror
+    if (LG >= 4) v = or_dpp<0x140>(v);  // row_mirror
+    if (LG >= 5) v |= (uint32_t)__shfl_xor((int)v, 16);
+    if (LG >= 6) v |= (uint32_t)__shfl_xor((int)v, 32);
+    return v;
 }
 
-// Lane-mask helpers for groups (a group = the LW consecutive lanes holding one cluster).
-// fold_or / fold_and leave, on the first lane of every group, the OR / AND of the group's bits.
-template <int NW>
-__device__ __forceinline__ uint64_t fold_or(const Ctx<NW> &x, uint64_t m)
+// Does some existing group of slot t have no set bit in the lane mask m?  (The zero-field test
+// (m - lo) & ~m & hi with one field per group.)
+template <int NW, int LG>
+__device__ __forceinline__ bool some_group_empty(const Ctx<NW> &x, int t, uint64_t m)
 {
-    for (int sh = 1; sh < (1 << x.log2lw); sh <<= 1) m |= m >> sh;
-    return m;
-}
-template <int NW>
-__device__ __forceinline__ uint64_t fold_and(const Ctx<NW> &x, uint64_t m)
-{
-    for (int sh = 1; sh < (1 << x.log2lw); sh <<= 1) m &= m >> sh;
-    return m;
+    constexpr int LW = 1 << LG;
+    uint64_t lo = 0;
+#pragma unroll
+    for (int g = 0; g < 64; g += LW) lo |= 1ull << g;
+    const uint64_t hi = lo << (LW - 1);
+    m |= ~x.validmask[t];
+    return ((m - lo) & ~m & hi) != 0;
 }
 
 // Lists the rows a pass must fetch in a register: lane i of `list` gets (row index + 1) of the
 // i-th entry, lanes past the end get 0.  Entries are, slot by slot, the set bits of pw[] (row =
 // neuron index, ascending) followed by one summary row (row n + c) for every lane flagged in
-// sumlane[] (the first lane of a fully active cluster c).  Returns the number of entries, or -1
+// summask[] (the first lane of a fully active cluster c).  Returns the number of entries, or -1
 // if there are more than kListMax (list is then unusable).
 template <int NW>
-__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], const bool (&sumlane)[NW],
+__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], const uint64_t (&summask)[NW],
                                           uint32_t &list)
 {
     int base = 0;
@@ -138,49 +155,85 @@ __device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)
             uint32_t w = pw[t];
             do {
                 const bool has = (w != 0u);
-                const uint32_t j = ((uint32_t)((t << 6) + x.lane) << 5) + (uint32_t)__builtin_ctz(w | 0x80000000u);
+                const uint32_t j = x.bit0[t] + (uint32_t)__builtin_ctz(w | 0x80000000u);
                 // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
                 list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
                 w &= w - 1u;
                 ++rank;
             } while (ballot(w != 0u));
         }
-        const uint64_t sm = ballot(sumlane[t]);
+        const uint64_t sm = summask[t];
         if (sm) {
             const uint32_t rank = (uint32_t)base + mbcnt(sm);
             base += __builtin_popcountll(sm);
             if (base > kListMax) return -1;
-            list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((sumlane[t] ? rank : 63u) << 2),
-                                                          (int)(sumlane[t] ? x.nrows + x.myc[t] + 1u : 0u));
+            const bool mine = lane_of(sm);
+            list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((mine ? rank : 63u) << 2),
+                                                          (int)(mine ? x.nrows + x.myc[t] + 1u : 0u));
         }
     }
     return base;
 }
 
+// B rows (entries i0 .. i0+B-1 of the per-lane offset list; i0+B <= 64) fetched together, ANDed into acc.
+template <int NW, int B>
+__device__ __forceinline__ void and_batch(const Ctx<NW> &x, uint32_t offv, int i0, uint32_t (&acc)[NW])
+{
+    uint32_t r[B][NW];
+#pragma unroll
+    for (int q = 0; q < B; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+#pragma unroll
+    for (int q = 0; q < B; ++q)
+#pragma unroll
+        for (int u = 0; u < NW; ++u) acc[u] &= r[q][u];
+}
+// B rows fetched together and folded into (R, acc): keep == 0 marks the first row of a cluster.
+template <int NW, int B>
+__device__ __forceinline__ void or_and_batch(const Ctx<NW> &x, uint32_t offv, uint32_t keepv, int i0,
+                                             uint32_t (&R)[NW], uint32_t (&acc)[NW])
+{
+    uint32_t r[B][NW];
+#pragma unroll
+    for (int q = 0; q < B; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+#pragma unroll
+    for (int q = 0; q < B; ++q) {
+        const uint32_t keep = readlane(keepv, i0 + q);
+#pragma unroll
+        for (int u = 0; u < NW; ++u) {
+            acc[u] &= R[u] | keep;
+            R[u] = (R[u] & keep) | r[q][u];
+        }
+    }
+}
+
 // acc &= , for every cluster c' with entries in the list, the OR of the rows of its entries.
 // The rows come from the copy of W whose intra-cluster blocks are all ones, so a neuron of c'
 // itself always passes.  Entries of one cluster are adjacent (the list is sorted by neuron index).
-template <int NW>
+template <int NW, int LG>
 __device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int total, uint32_t (&acc)[NW])
 {
-    // Lanes past the end repeat the last entry, so the loop below can always fetch kInFlight rows.
+    // Lanes past the end repeat the last entry, so the loop below can always fetch whole batches.
     const uint32_t jlast = readlane(list, total - 1) - 1u;
     const uint32_t jv = (x.lane < total) ? list - 1u : jlast;
-    const uint32_t offv = jv * x.rowbytes;
-    const uint32_t cv = (jv >= x.nrows) ? jv : (jv >> x.log2L);  // a summary row is a cluster of its own
-    const uint32_t prev = (uint32_t)__shfl_up((int)cv, 1);
-    const bool isfirst = (x.lane == 0) || (cv != prev);  // entry starts a new cluster
+    const uint32_t offv = __umul24(jv, x.rowbytes);
+    const uint32_t cv = (jv >= x.nrows) ? jv : (jv >> (LG + 5));  // a summary row is a cluster of its own
+    // cluster of the previous entry: the value of the lane below (lane 0 keeps the "none" value)
+    const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)cv, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+    const bool isfirst = (cv != prev);  // entry starts a new cluster
     const uint64_t first = ballot(isfirst);
+    // Rows are fetched 8 at a time (4 for a short tail): the pass is bound by the number of
+    // dependent memory round trips, not by the few redundant loads of the last batch.
     if (__builtin_popcountll(first) == total) {
         // every cluster lists one row: plain AND of the rows
-        for (int i0 = 0; i0 < total; i0 += kInFlight) {
-            uint32_t r[kInFlight][NW];
-#pragma unroll
-            for (int q = 0; q < kInFlight; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
-#pragma unroll
-            for (int q = 0; q < kInFlight; ++q)
-#pragma unroll
-                for (int u = 0; u < NW; ++u) acc[u] &= r[q][u];
+        int i0 = 0;
+        while (i0 < total) {
+            if (total - i0 > 4) {
+                and_batch<NW, 8>(x, offv, i0, acc);
+                i0 += 8;
+            } else {
+                and_batch<NW, 4>(x, offv, i0, acc);
+                i0 += 4;
+            }
         }
         return;
     }
@@ -190,18 +243,14 @@ __device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int 
     uint32_t R[NW];
 #pragma unroll
     for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
-    for (int i0 = 0; i0 < total; i0 += kInFlight) {
-        uint32_t r[kInFlight][NW];
-#pragma unroll
-        for (int q = 0; q < kInFlight; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
-#pragma unroll
-        for (int q = 0; q < kInFlight; ++q) {
-            const uint32_t keep = readlane(keepv, i0 + q);
-#pragma unroll
-            for (int u = 0; u < NW; ++u) {
-                acc[u] &= R[u] | keep;
-                R[u] = (R[u] & keep) | r[q][u];
-            }
+    int i0 = 0;
+    while (i0 < total) {
+        if (total - i0 > 4) {
+            or_and_batch<NW, 8>(x, offv, keepv, i0, R, acc);
+            i0 += 8;
+        } else {
+            or_and_batch<NW, 4>(x, offv, keepv, i0, R, acc);
+            i0 += 4;
         }
     }
 #pragma unroll
@@ -209,9 +258,9 @@ __device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int 
 }
 
 // The same, with scalar enumeration and one row in flight: for more rows than the list holds.
-template <int NW>
+template <int NW, int LG>
 __device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32_t (&pw)[NW],
-                                                  const bool (&sumlane)[NW], uint32_t (&acc)[NW])
+                                                  const uint64_t (&summask)[NW], uint32_t (&acc)[NW])
 {
     uint32_t R[NW];
 #pragma unroll
@@ -224,7 +273,7 @@ __device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32
             const int sl = __builtin_ctzll(lanes);
             lanes &= lanes - 1;
             uint32_t word = readlane(pw[t], sl);
-            const int c = (t << 6 | sl) >> x.log2lw;
+            const int c = (t << 6 | sl) >> LG;
             if (c != curc) {
 #pragma unroll
                 for (int u = 0; u < NW; ++u) {
@@ -242,8 +291,8 @@ __device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32
                 for (int u = 0; u < NW; ++u) R[u] |= r[u];
             }
         }
-        for (uint64_t sm = ballot(sumlane[t]); sm; sm &= sm - 1) {
-            const uint32_t c = (uint32_t)(t * x.cps + (__builtin_ctzll(sm) >> x.log2lw));
+        for (uint64_t sm = summask[t]; sm; sm &= sm - 1) {
+            const uint32_t c = (uint32_t)((t << 6 | __builtin_ctzll(sm)) >> LG);
             uint32_t r[NW];
             load_row(x, x.wbrsrc, (x.nrows + c) * x.rowbytes, r);
 #pragma unroll
@@ -254,40 +303,56 @@ __device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32
     for (int u = 0; u < NW; ++u) acc[u] &= R[u];
 }
 
-// One sum-of-max pass over the dirty clusters: acc = v AND, for each dirty cluster c',
-// (OR of rows of active neurons of c'  |  own-cluster mask of c').
-template <int NW>
-__device__ __forceinline__ void som_pass(const Ctx<NW> &x, const uint32_t (&v)[NW], const uint64_t (&dirty)[NW],
+// acc &= , for every cluster with a word in pw[] or a lane in summask[], what that cluster lets survive.
+template <int NW, int LG>
+__device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, const uint32_t (&pw)[NW],
+                                                const uint64_t (&summask)[NW], uint32_t (&acc)[NW])
+{
+    uint32_t list;
+    const int total = build_list(x, pw, summask, list);
+    if (total > 0) apply_rows<NW, LG>(x, list, total, acc);
+    else if (total < 0) apply_rows_serial<NW, LG>(x, pw, summask, acc);
+}
+
+// One sum-of-max pass from the second on.  d[] is nonzero in the lanes that changed in the previous
+// pass; only the clusters holding such a lane ("dirty") can switch anything off (Lemma 1).
+//   acc = v AND over dirty clusters c' of (OR of the rows of the active neurons of c' | own mask of c')
+// A cluster without any active neuron signals nobody, so every neuron outside it goes off, and it
+// holds none itself: acc = 0.
+template <int NW, int LG>
+__device__ __forceinline__ void som_step(const Ctx<NW> &x, const uint32_t (&v)[NW], const uint32_t (&d)[NW],
                                          uint32_t (&acc)[NW])
 {
-    uint32_t pw[NW];   // words that list rows to fetch: active words of dirty, not fully active clusters
-    bool sumlane[NW];  // first lane of a dirty, fully active cluster: fetch its summary row instead
+    bool dead = false;
+#pragma unroll
+    for (int t = 0; t < NW; ++t) dead = dead || some_group_empty<NW, LG>(x, t, ballot(v[t] != 0u));
+    if (dead) {
+#pragma unroll
+        for (int t = 0; t < NW; ++t) acc[t] = 0u;
+        return;
+    }
+    uint32_t pw[NW];
+    uint64_t summask[NW];
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
         acc[t] = v[t];
-        pw[t] = 0u;
-        sumlane[t] = false;
-        if (dirty[t] == 0) continue;
-        const uint64_t notfull = ballot(v[t] != 0xFFFFFFFFu);
-        const uint64_t nz = ballot(v[t] != 0u);
-        const bool gdirty = group_any(x, dirty[t]);
-        // Fully active cluster (an erased cluster at the start of sum-of-max, Section III-C): what
-        // survives it is its stored summary row.
-        const bool gfull = !group_any(x, notfull);
-        if (gdirty && !gfull) pw[t] = v[t];
-        sumlane[t] = gdirty && gfull && x.valid[t] && (x.lane == x.grpstart);
-        // A dirty cluster with no active neuron signals nobody: everything outside it goes off.
-        uint64_t empty_leads = ballot(gdirty && !group_any(x, nz) && x.valid[t] && (x.lane == x.grpstart));
-        for (; empty_leads; empty_leads &= empty_leads - 1) {
-            const uint32_t c = (uint32_t)(t * x.cps + (__builtin_ctzll(empty_leads) >> x.log2lw));
-#pragma unroll
-            for (int u = 0; u < NW; ++u) acc[u] &= (x.myc[u] == c) ? 0xFFFFFFFFu : 0u;
-        }
+        pw[t] = group_or<LG>(d[t]) ? v[t] : 0u;
+        summask[t] = 0;
     }
-    uint32_t list;
-    const int total = build_list(x, pw, sumlane, list);
-    if (total > 0) apply_rows(x, list, total, acc);
-    else if (total < 0) apply_rows_serial(x, pw, sumlane, acc);
+    fetch_and_apply<NW, LG>(x, pw, summask, acc);
+}
+
+// d = a ^ b; returns whether they differ anywhere.
+template <int NW>
+__device__ __forceinline__ bool diff(const uint32_t (&a)[NW], const uint32_t (&b)[NW], uint32_t (&d)[NW])
+{
+    uint64_t any = 0;
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        d[t] = a[t] ^ b[t];
+        any |= ballot(d[t] != 0u);
+    }
+    return any != 0;
 }
 
 // Bit-sliced sum over the rows of all active neurons: pl[p] holds digit p of
@@ -330,47 +395,32 @@ __device__ __forceinline__ int count_signals(const Ctx<NW> &x, const uint32_t (&
     return rows;
 }
 
-template <int NW>
-__device__ __forceinline__ bool any_diff(const uint32_t (&a)[NW], const uint32_t (&b)[NW], uint64_t (&lanes)[NW])
+// NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
+template <int NW, int RULE, int LG>
+__global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a)
 {
-    uint64_t any = 0;
-#pragma unroll
-    for (int t = 0; t < NW; ++t) {
-        lanes[t] = ballot(a[t] != b[t]);
-        any |= lanes[t];
-    }
-    return any != 0;
-}
-
-template <int NW, int RULE>
-__global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2lw)
-{
+    constexpr int LW = 1 << LG;
+    constexpr int CPS = 64 / LW;  // clusters per slot
     Ctx<NW> x;
-    x.nw = a.nw;
-    x.C = a.C;
     x.rowbytes = (uint32_t)a.nw * 4u;
+    x.nrows = (uint32_t)a.n;
     x.wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.W), 0, (int)((uint32_t)a.n * x.rowbytes),
                                                 0x00020000);
-    x.nrows = (uint32_t)a.n;
     x.wbrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
                                                  (int)((uint32_t)(a.n + a.C) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
-    x.log2lw = log2lw;
-    x.log2L = log2lw + 5;
-    x.cps = 64 >> log2lw;
-    x.grp = x.lane >> log2lw;
-    x.grpstart = x.grp << log2lw;
-    x.grpmask = (log2lw == 6) ? ~0ull : ((1ull << (1 << log2lw)) - 1ull);
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
         x.valid[t] = (t * 64 + x.lane) < a.nw;
+        x.islead[t] = x.valid[t] && (x.lane & (LW - 1)) == 0;
         x.woffb[t] = x.valid[t] ? (uint32_t)(t * 64 + x.lane) * 4u : 0u;
-        x.myc[t] = x.valid[t] ? (uint32_t)(t * x.cps + x.grp) : 0xFFFFu;
+        x.myc[t] = x.valid[t] ? (uint32_t)(t * CPS + (x.lane >> LG)) : 0xFFFFu;
+        x.bit0[t] = (uint32_t)(t * 64 + x.lane) << 5;
         x.validmask[t] = ballot(x.valid[t]);
-        x.lead[t] = ballot(x.valid[t] && (x.lane == x.grpstart));
     }
-    const int64_t wave = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int wpb = (int)(blockDim.x >> 6);  // waves per workgroup
+    const int64_t wave = (int64_t)blockIdx.x * wpb + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t nwaves = (int64_t)gridDim.x * wpb;
 
     for (int64_t k = wave; k < a.K; k += nwaves) {
         // ---- probe load: 32 bytes per word, packed to bits
@@ -385,94 +435,87 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
         }
 
         int it = 0;
-        if (RULE == GBNN_SUM_OF_MAX) {
-            // Section III-C: clusters with no active neuron start fully active.
-            uint64_t dirty[NW];
+        if (RULE == GBNN_SUM_OF_MAX || RULE == GBNN_HYBRID) {
+            // Erased clusters = clusters with no active neuron in the probe.
+            bool erased[NW];
 #pragma unroll
-            for (int t = 0; t < NW; ++t) {
-                const uint64_t nz = ballot(v[t] != 0u);
-                if (x.valid[t] && !group_any(x, nz)) v[t] = 0xFFFFFFFFu;
-                dirty[t] = x.validmask[t];
+            for (int t = 0; t < NW; ++t) erased[t] = x.valid[t] && group_or<LG>(v[t]) == 0u;
+            uint32_t acc[NW], d[NW];
+            int p = 1;
+            bool changed = true;
+            if (RULE == GBNN_SUM_OF_MAX) {
+                // Section III-C: erased clusters start fully active.  Pass 1: the known clusters
+                // contribute the rows of their active neurons, the (fully active) erased clusters
+                // their summary rows.
+                uint32_t pw[NW];
+                uint64_t summask[NW];
+#pragma unroll
+                for (int t = 0; t < NW; ++t) {
+                    pw[t] = v[t];
+                    summask[t] = ballot(erased[t] && x.islead[t]);
+                    if (erased[t]) v[t] = 0xFFFFFFFFu;
+                    acc[t] = v[t];
+                }
+                fetch_and_apply<NW, LG>(x, pw, summask, acc);
+                changed = diff(acc, v, d);
+            } else {
+                // Algorithm 2, lines 1-5.
+                int known = 0, nzlanes = 0;
+                uint64_t multi = 0;
+#pragma unroll
+                for (int t = 0; t < NW; ++t) {
+                    known += __builtin_popcountll(ballot(x.islead[t] && !erased[t]));
+                    nzlanes += __builtin_popcountll(ballot(v[t] != 0u));
+                    multi |= ballot((v[t] & (v[t] - 1u)) != 0u);
+                }
+                if (!multi && nzlanes == known) {
+                    // Every known cluster holds exactly one active neuron (the probe contract).  Then
+                    // "exactly C - e signals" means "adjacent to every known active neuron": the AND of
+                    // their rows over the erased clusters.
+                    uint64_t summask[NW];
+#pragma unroll
+                    for (int t = 0; t < NW; ++t) {
+                        acc[t] = erased[t] ? 0xFFFFFFFFu : v[t];
+                        summask[t] = 0;
+                    }
+                    fetch_and_apply<NW, LG>(x, v, summask, acc);
+#pragma unroll
+                    for (int t = 0; t < NW; ++t) {
+                        acc[t] = erased[t] ? acc[t] : v[t];
+                        d[t] = erased[t] ? 1u : 0u;  // known clusters have just been applied: clean
+                    }
+                } else {
+                    // General probe: count the signals with bit-sliced counters, keep "== C - e".
+                    uint32_t pl[kPlanes][NW];
+                    const int rows = count_signals(x, v, pl);
+                    const int np = rows ? 32 - __builtin_clz((unsigned)rows) : 0;
+#pragma unroll
+                    for (int u = 0; u < NW; ++u) {
+                        uint32_t eq = 0xFFFFFFFFu;
+#pragma unroll
+                        for (int q = 0; q < kPlanes; ++q) {
+                            if (q >= np) break;
+                            eq &= ((known >> q) & 1) ? pl[q][u] : ~pl[q][u];
+                        }
+                        acc[u] = erased[u] ? eq : v[u];
+                        d[u] = x.valid[u] ? 1u : 0u;
+                    }
+                }
+                // the stop test is made only after a bail-out-early pass (Algorithm 2, line 13)
             }
-            int p = 0;
             for (;;) {
-                uint32_t acc[NW];
-                som_pass(x, v, dirty, acc);
-                ++p;
-                const bool changed = any_diff(acc, v, dirty);
 #pragma unroll
                 for (int t = 0; t < NW; ++t) v[t] = acc[t];
                 if (!changed) { it = p; break; }
                 if (p == a.max_iters) { it = -p; break; }
-            }
-        } else if (RULE == GBNN_HYBRID) {
-            // Algorithm 2.  Erased clusters = clusters with no active neuron in the probe.
-            bool erased[NW];
-            uint64_t erasedmask[NW];
-            uint64_t dirty[NW];
-            int known = 0, nzlanes = 0;
-            bool onehot = true;
-#pragma unroll
-            for (int t = 0; t < NW; ++t) {
-                const uint64_t nz = ballot(v[t] != 0u);
-                const uint64_t single = ballot(v[t] != 0u && (v[t] & (v[t] - 1u)) == 0u);
-                onehot = onehot && (single == nz);
-                nzlanes += __builtin_popcountll(nz);
-                erased[t] = x.valid[t] && !group_any(x, nz);
-                erasedmask[t] = ballot(erased[t]);
-                known += __builtin_popcountll(fold_or(x, nz) & x.lead[t]);
-            }
-            if (onehot && nzlanes == known) {
-                // Every known cluster holds exactly one active neuron (the probe contract).  Then
-                // "exactly C - e signals" (lines 2-5) means "adjacent to every known active neuron":
-                // the AND of their rows, which is a sum-of-max pass over the known clusters applied
-                // to fully active erased clusters.
-                uint32_t vi[NW], acc[NW];
-#pragma unroll
-                for (int t = 0; t < NW; ++t) {
-                    vi[t] = erased[t] ? 0xFFFFFFFFu : v[t];
-                    dirty[t] = x.validmask[t] & ~erasedmask[t];
-                }
-                som_pass(x, vi, dirty, acc);
-#pragma unroll
-                for (int t = 0; t < NW; ++t) {
-                    if (erased[t]) v[t] = acc[t];
-                    dirty[t] = erasedmask[t];  // known clusters have just been applied: clean
-                }
-            } else {
-                // General probe: count the signals with bit-sliced counters, keep "== C - e".
-                uint32_t pl[kPlanes][NW];
-                const int rows = count_signals(x, v, pl);
-                const int np = rows ? 32 - __builtin_clz((unsigned)rows) : 0;
-#pragma unroll
-                for (int u = 0; u < NW; ++u) {
-                    uint32_t eq = 0xFFFFFFFFu;
-#pragma unroll
-                    for (int p = 0; p < kPlanes; ++p) {
-                        if (p >= np) break;
-                        eq &= ((known >> p) & 1) ? pl[p][u] : ~pl[p][u];
-                    }
-                    if (erased[u]) v[u] = eq;
-                    dirty[u] = x.validmask[u];
-                }
-            }
-            int p = 1;
-            if (p == a.max_iters) {
-                it = -p;
-            } else {
-                for (;;) {
-                    uint32_t acc[NW];
-                    som_pass(x, v, dirty, acc);
+                som_step<NW, LG>(x, v, d, acc);
+                if (RULE == GBNN_HYBRID) {
 #pragma unroll
                     for (int t = 0; t < NW; ++t)
                         if (!erased[t]) acc[t] = v[t];  // known clusters are frozen
-                    ++p;
-                    const bool changed = any_diff(acc, v, dirty);
-#pragma unroll
-                    for (int t = 0; t < NW; ++t) v[t] = acc[t];
-                    if (!changed) { it = p; break; }
-                    if (p == a.max_iters) { it = -p; break; }
                 }
+                ++p;
+                changed = diff(acc, v, d);
             }
         } else {
             // Algorithm 1 with Eq. (3)-(5).
@@ -490,9 +533,9 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
                         for (int q = 0; q < kPlanes; ++q) {
                             if (q >= P) break;
                             const uint32_t g = ((a.gamma >> q) & 1) ? v[u] : 0u;
-                            const uint32_t d = pl[q][u];
-                            pl[q][u] = d ^ g ^ cy;
-                            cy = (d & g) | (cy & (d ^ g));
+                            const uint32_t dg = pl[q][u];
+                            pl[q][u] = dg ^ g ^ cy;
+                            cy = (dg & g) | (cy & (dg ^ g));
                         }
                     }
                 }
@@ -506,13 +549,12 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
 #pragma unroll
                     for (int u = 0; u < NW; ++u) {
                         const uint32_t tt = cand[u] & pl[q][u];
-                        const uint64_t nzm = ballot(tt != 0u);
-                        if (group_any(x, nzm)) cand[u] = tt;
+                        if (group_or<LG>(tt) != 0u) cand[u] = tt;
                     }
                 }
                 ++p;
-                uint64_t diff[NW];
-                const bool changed = any_diff(cand, v, diff);
+                uint32_t d[NW];
+                const bool changed = diff(cand, v, d);
 #pragma unroll
                 for (int t = 0; t < NW; ++t) v[t] = cand[t];
                 if (!changed) { it = p; break; }
@@ -534,29 +576,49 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a, int log2l
     }
 }
 
-template <int NW>
-hipError_t launch_nw(const RetrieveArgs &a, int log2lw, hipStream_t s)
+template <int NW, int LG>
+hipError_t launch_one(const RetrieveArgs &a, hipStream_t s)
 {
-    int64_t blocks = (a.K + 3) / 4;
-    int64_t cap = 256 * 8;  // 256 CUs x 8 workgroups of 4 waves = every wave slot of the chip
+    int wpb = 4;
+    if (const char *e = std::getenv("GBNN_BLOCK_WAVES")) {  // tuning aid
+        const long v = std::atol(e);
+        if (v >= 1 && v <= 4) wpb = (int)v;
+    }
+    int64_t blocks = (a.K + wpb - 1) / wpb;
+    int64_t cap = 1 << 20;
     if (const char *e = std::getenv("GBNN_GRID_BLOCKS")) {  // tuning aid
         const long v = std::atol(e);
         if (v > 0) cap = v;
     }
     if (blocks > cap) blocks = cap;
-    const dim3 grid((unsigned)blocks), block(256);
+    const dim3 grid((unsigned)blocks), block(64 * wpb);
     switch (a.rule) {
     case GBNN_SUM_OF_SUM:
-        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_SUM_OF_SUM>), grid, block, 0, s, a, log2lw);
+        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_SUM_OF_SUM, LG>), grid, block, 0, s, a);
         break;
     case GBNN_SUM_OF_MAX:
-        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_SUM_OF_MAX>), grid, block, 0, s, a, log2lw);
+        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_SUM_OF_MAX, LG>), grid, block, 0, s, a);
         break;
     default:
-        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_HYBRID>), grid, block, 0, s, a, log2lw);
+        hipLaunchKernelGGL((k_retrieve_wave<NW, GBNN_HYBRID, LG>), grid, block, 0, s, a);
         break;
     }
     return hipGetLastError();
+}
+
+template <int NW>
+hipError_t launch_nw(const RetrieveArgs &a, int log2lw, hipStream_t s)
+{
+    switch (log2lw) {
+    case 0: return launch_one<NW, 0>(a, s);
+    case 1: return launch_one<NW, 1>(a, s);
+    case 2: return launch_one<NW, 2>(a, s);
+    case 3: return launch_one<NW, 3>(a, s);
+    case 4: return launch_one<NW, 4>(a, s);
+    case 5: return launch_one<NW, 5>(a, s);
+    case 6: return launch_one<NW, 6>(a, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
