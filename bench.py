@@ -39,7 +39,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3", help="cfg3 (default), cfg4_m10k, cfg4_m30k, cfg4_m50k, cfg5, cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the untimed per-workload side measurements")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 3 plain device copies of the probe tensor (K*n bytes read, K*n written) after the "
+                         "timed region: the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (probes are independent, so more GPUs would just "
@@ -117,6 +119,14 @@ def main() -> int:
     tfile = ROOT / "profiles" / "hbm_traffic.json"
     if tfile.exists():
         traffic = json.loads(tfile.read_text()).get(f"{args.workload}:{dominant}")
+
+    if args.calibrate_copy:
+        for _ in range(3):
+            outs[rules[0]].view(torch.int64).copy_(V0d.view(torch.int64))  # 8-byte elements: full-width stores
+        torch.cuda.synchronize()
+        for r in rules[:1]:
+            call(r)  # restore the result the copy overwrote
+        torch.cuda.synchronize()
 
     # ---- outcome of the retrieval (outside the timed region)
     target_idx = torch.from_numpy(inputs.active_neurons(msgs[q], L)).cuda()
