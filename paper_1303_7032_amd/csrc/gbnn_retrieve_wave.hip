@@ -126,19 +126,22 @@ __device__ __forceinline__ bool some_group_empty(const Ctx<NW> &x, int t, uint64
     return ((m - lo) & ~m & hi) != 0;
 }
 
-// Lists the rows a pass must fetch in a register: lane i of `list` gets (row index + 1) of the
-// i-th entry, lanes past the end get 0.  Entries are, slot by slot, the set bits of pw[] (row =
-// neuron index, ascending) followed by one summary row (row n + c) for every lane flagged in
-// summask[] (the first lane of a fully active cluster c).  Returns the number of entries, or -1
-// if there are more than kListMax (list is then unusable).
+// Takes the next chunk of rows a pass must fetch into a register list: lane i of `list` gets
+// (row index + 1) of the i-th entry, lanes past the end get 0.  Entries are, slot by slot, the set
+// bits of pw[] (row = neuron index, ascending) followed by one summary row (row n + c) for every
+// lane flagged in summask[] (the first lane of a fully active cluster c).  At most kListMax
+// entries are taken, whole words at a time and in order; what is taken is cleared from pw[] and
+// summask[], so that calling again continues where this chunk stopped.  Returns the entry count.
 template <int NW>
-__device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)[NW], const uint64_t (&summask)[NW],
+__device__ __forceinline__ int take_chunk(const Ctx<NW> &x, uint32_t (&pw)[NW], uint64_t (&summask)[NW],
                                           uint32_t &list)
 {
     int base = 0;
+    bool open = true;  // false once something had to be left for the next chunk
     list = 0u;
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
+        if (!open) break;
         const uint32_t pc = __popc(pw[t]);
         uint64_t mk = ballot(pc > 0u);
         if (mk) {
@@ -150,24 +153,38 @@ __device__ __forceinline__ int build_list(const Ctx<NW> &x, const uint32_t (&pw)
                 tot += __builtin_popcountll(mk);
                 mk = ballot(pc > k);
             }
-            base += tot;
-            if (base > kListMax) return -1;
             uint32_t w = pw[t];
-            do {
+            if (base + tot > kListMax) {
+                // keep the words that fit entirely; the rest of this slot and all later slots wait
+                const bool fits = rank + pc <= (uint32_t)kListMax;
+                w = fits ? w : 0u;
+                tot = 0;
+                mk = ballot(w != 0u);
+                for (uint32_t k = 1; mk; ++k) {
+                    tot += __builtin_popcountll(mk);
+                    mk = ballot(fits && pc > k);
+                }
+                open = false;
+            }
+            pw[t] &= ~w;
+            base += tot;
+            while (ballot(w != 0u)) {
                 const bool has = (w != 0u);
                 const uint32_t j = x.bit0[t] + (uint32_t)__builtin_ctz(w | 0x80000000u);
                 // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
                 list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
                 w &= w - 1u;
                 ++rank;
-            } while (ballot(w != 0u));
+            }
         }
         const uint64_t sm = summask[t];
-        if (sm) {
+        if (open && sm) {
             const uint32_t rank = (uint32_t)base + mbcnt(sm);
-            base += __builtin_popcountll(sm);
-            if (base > kListMax) return -1;
-            const bool mine = lane_of(sm);
+            const bool mine = lane_of(sm) && rank < (uint32_t)kListMax;
+            const uint64_t taken = ballot(mine);
+            summask[t] = sm & ~taken;
+            open = (summask[t] == 0);
+            base += __builtin_popcountll(taken);
             list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((mine ? rank : 63u) << 2),
                                                           (int)(mine ? x.nrows + x.myc[t] + 1u : 0u));
         }
@@ -206,112 +223,70 @@ __device__ __forceinline__ void or_and_batch(const Ctx<NW> &x, uint32_t offv, ui
     }
 }
 
-// acc &= , for every cluster c' with entries in the list, the OR of the rows of its entries.
-// The rows come from the copy of W whose intra-cluster blocks are all ones, so a neuron of c'
-// itself always passes.  Entries of one cluster are adjacent (the list is sorted by neuron index).
+// acc &= , for every cluster with a word in pw[] or a lane in summask[], what that cluster lets
+// survive: the OR of the rows of its listed neurons, or its summary row.  The rows come from the
+// copy of W whose intra-cluster blocks are all ones, so a neuron of the cluster itself always
+// passes.  Rows are listed in chunks of up to kListMax and fetched 8 at a time (4 for a short
+// tail): a pass is bound by its dependent memory round trips, not by a few redundant loads.
+// Entries of one cluster are adjacent (ascending neuron index) but may straddle chunks: R holds
+// the OR of the cluster in progress and prevc its number.  pw[] and summask[] are consumed.
 template <int NW, int LG>
-__device__ __forceinline__ void apply_rows(const Ctx<NW> &x, uint32_t list, int total, uint32_t (&acc)[NW])
+__device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, uint32_t (&pw)[NW], uint64_t (&summask)[NW],
+                                                uint32_t (&acc)[NW])
 {
-    // Lanes past the end repeat the last entry, so the loop below can always fetch whole batches.
-    const uint32_t jlast = readlane(list, total - 1) - 1u;
-    const uint32_t jv = (x.lane < total) ? list - 1u : jlast;
-    const uint32_t offv = __umul24(jv, x.rowbytes);
-    const uint32_t cv = (jv >= x.nrows) ? jv : (jv >> (LG + 5));  // a summary row is a cluster of its own
-    // cluster of the previous entry: the value of the lane below (lane 0 keeps the "none" value)
-    const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)cv, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
-    const bool isfirst = (cv != prev);  // entry starts a new cluster
-    const uint64_t first = ballot(isfirst);
-    // Rows are fetched 8 at a time (4 for a short tail): the pass is bound by the number of
-    // dependent memory round trips, not by the few redundant loads of the last batch.
-    if (__builtin_popcountll(first) == total) {
-        // every cluster lists one row: plain AND of the rows
+    uint32_t R[NW];
+#pragma unroll
+    for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
+    uint32_t prevc = 0xFFFFFFFFu;
+    bool first_chunk = true;
+    for (;;) {
+        uint32_t list;
+        const int total = take_chunk(x, pw, summask, list);
+        if (total == 0) break;
+        uint64_t rest = 0;
+#pragma unroll
+        for (int t = 0; t < NW; ++t) rest |= ballot(pw[t] != 0u) | summask[t];
+        // Lanes past the end repeat the last entry, so that whole batches can always be fetched.
+        const uint32_t jlast = readlane(list, total - 1) - 1u;
+        const uint32_t jv = (x.lane < total) ? list - 1u : jlast;
+        const uint32_t offv = __umul24(jv, x.rowbytes);
+        const uint32_t cv = (jv >= x.nrows) ? jv : (jv >> (LG + 5));  // a summary row is a cluster of its own
+        // cluster of the previous entry: the value of the lane below (lane 0: the last one of the previous chunk)
+        const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)prevc, (int)cv, 0x138 /* wave_shr:1 */, 0xf,
+                                                                    0xf, false);
+        const bool isfirst = (cv != prev);  // entry starts a new cluster
         int i0 = 0;
+        if (first_chunk && !rest && __builtin_popcountll(ballot(isfirst)) == total) {
+            // the usual case: one chunk and every cluster lists one row: plain AND of the rows
+            while (i0 < total) {
+                if (total - i0 > 4) {
+                    and_batch<NW, 8>(x, offv, i0, acc);
+                    i0 += 8;
+                } else {
+                    and_batch<NW, 4>(x, offv, i0, acc);
+                    i0 += 4;
+                }
+            }
+            return;
+        }
+        // General case, branch-free: R collects the OR of the current cluster's rows; at the first
+        // row of the next cluster (keep == 0) it is ANDed into acc and restarted.
+        const uint32_t keepv = isfirst ? 0u : 0xFFFFFFFFu;
         while (i0 < total) {
             if (total - i0 > 4) {
-                and_batch<NW, 8>(x, offv, i0, acc);
+                or_and_batch<NW, 8>(x, offv, keepv, i0, R, acc);
                 i0 += 8;
             } else {
-                and_batch<NW, 4>(x, offv, i0, acc);
+                or_and_batch<NW, 4>(x, offv, keepv, i0, R, acc);
                 i0 += 4;
             }
         }
-        return;
-    }
-    // General case, branch-free: R collects the OR of the current cluster's rows; at the first row
-    // of the next cluster (keep == 0) it is ANDed into acc and restarted.
-    const uint32_t keepv = isfirst ? 0u : 0xFFFFFFFFu;
-    uint32_t R[NW];
-#pragma unroll
-    for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
-    int i0 = 0;
-    while (i0 < total) {
-        if (total - i0 > 4) {
-            or_and_batch<NW, 8>(x, offv, keepv, i0, R, acc);
-            i0 += 8;
-        } else {
-            or_and_batch<NW, 4>(x, offv, keepv, i0, R, acc);
-            i0 += 4;
-        }
+        if (!rest) break;
+        prevc = readlane(cv, total - 1);
+        first_chunk = false;
     }
 #pragma unroll
     for (int u = 0; u < NW; ++u) acc[u] &= R[u];
-}
-
-// The same, with scalar enumeration and one row in flight: for more rows than the list holds.
-template <int NW, int LG>
-__device__ __forceinline__ void apply_rows_serial(const Ctx<NW> &x, const uint32_t (&pw)[NW],
-                                                  const uint64_t (&summask)[NW], uint32_t (&acc)[NW])
-{
-    uint32_t R[NW];
-#pragma unroll
-    for (int u = 0; u < NW; ++u) R[u] = 0xFFFFFFFFu;
-    int curc = -1;
-#pragma unroll
-    for (int t = 0; t < NW; ++t) {
-        uint64_t lanes = ballot(pw[t] != 0u);
-        while (lanes) {
-            const int sl = __builtin_ctzll(lanes);
-            lanes &= lanes - 1;
-            uint32_t word = readlane(pw[t], sl);
-            const int c = (t << 6 | sl) >> LG;
-            if (c != curc) {
-#pragma unroll
-                for (int u = 0; u < NW; ++u) {
-                    acc[u] &= R[u];
-                    R[u] = 0u;
-                }
-                curc = c;
-            }
-            while (word) {
-                const uint32_t j = ((uint32_t)(t << 6 | sl) << 5) + (uint32_t)__builtin_ctz(word);
-                word &= word - 1;
-                uint32_t r[NW];
-                load_row(x, x.wbrsrc, j * x.rowbytes, r);
-#pragma unroll
-                for (int u = 0; u < NW; ++u) R[u] |= r[u];
-            }
-        }
-        for (uint64_t sm = summask[t]; sm; sm &= sm - 1) {
-            const uint32_t c = (uint32_t)((t << 6 | __builtin_ctzll(sm)) >> LG);
-            uint32_t r[NW];
-            load_row(x, x.wbrsrc, (x.nrows + c) * x.rowbytes, r);
-#pragma unroll
-            for (int u = 0; u < NW; ++u) acc[u] &= r[u];
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < NW; ++u) acc[u] &= R[u];
-}
-
-// acc &= , for every cluster with a word in pw[] or a lane in summask[], what that cluster lets survive.
-template <int NW, int LG>
-__device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, const uint32_t (&pw)[NW],
-                                                const uint64_t (&summask)[NW], uint32_t (&acc)[NW])
-{
-    uint32_t list;
-    const int total = build_list(x, pw, summask, list);
-    if (total > 0) apply_rows<NW, LG>(x, list, total, acc);
-    else if (total < 0) apply_rows_serial<NW, LG>(x, pw, summask, acc);
 }
 
 // One sum-of-max pass from the second on.  d[] is nonzero in the lanes that changed in the previous
@@ -472,13 +447,15 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a)
                     // Every known cluster holds exactly one active neuron (the probe contract).  Then
                     // "exactly C - e signals" means "adjacent to every known active neuron": the AND of
                     // their rows over the erased clusters.
+                    uint32_t pw[NW];
                     uint64_t summask[NW];
 #pragma unroll
                     for (int t = 0; t < NW; ++t) {
                         acc[t] = erased[t] ? 0xFFFFFFFFu : v[t];
+                        pw[t] = v[t];
                         summask[t] = 0;
                     }
-                    fetch_and_apply<NW, LG>(x, v, summask, acc);
+                    fetch_and_apply<NW, LG>(x, pw, summask, acc);
 #pragma unroll
                     for (int t = 0; t < NW; ++t) {
                         acc[t] = erased[t] ? acc[t] : v[t];
