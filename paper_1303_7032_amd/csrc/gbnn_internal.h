@@ -23,12 +23,13 @@ struct RetrieveArgs {
     int rule, gamma, max_iters;
 };
 
-// Workspace layout: one table of n + C rows of nw words.  Rows 0..n-1: W with all-one intra-cluster
-// blocks; rows n..n+C-1: the cluster summaries.  (One table, so that one buffer resource reaches both.)
+// Workspace layout: one table of n + C + 1 rows of nw words.  Rows 0..n-1: W with all-one intra-cluster
+// blocks; rows n..n+C-1: the cluster summaries; row n+C: all zero (what the padding entries of a batch of
+// row fetches read when rows are counted).  One table, so that one buffer resource reaches all of it.
 inline size_t workspace_has_offset(int C, int L, int nw) { return (size_t)C * L * nw * sizeof(uint32_t); }
 inline size_t workspace_total_bytes(int C, int L, int nw)
 {
-    return (((size_t)C * L + C) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
+    return (((size_t)C * L + C + 1) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
 
 // Which kernel family serves a shape: 0 = generic, otherwise packed words per lane (1, 2, 4).

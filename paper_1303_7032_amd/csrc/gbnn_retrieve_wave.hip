@@ -66,11 +66,12 @@ __device__ __forceinline__ uint4 spread16(uint32_t h)
 
 template <int NW>
 struct Ctx {
-    __amdgpu_buffer_rsrc_t wrsrc;    // W as a raw buffer: loads beyond its end return 0
-    __amdgpu_buffer_rsrc_t wbrsrc;   // rows 0..n-1: W with all-one intra-cluster blocks; rows n..n+C-1: the
-                                     // cluster summaries (own-cluster bits included)
+    __amdgpu_buffer_rsrc_t wbrsrc;   // the prepared table as a raw buffer.  Rows 0..n-1: W with all-one
+                                     // intra-cluster blocks; rows n..n+C-1: the cluster summaries (own-cluster
+                                     // bits included); row n+C: all zero
     uint32_t rowbytes;               // nw * 4
     uint32_t nrows;                  // n
+    uint32_t nclusters;              // C
     int lane;
     bool valid[NW];          // this lane's word of slot t exists
     bool islead[NW];         // ... and is the first word of its cluster
@@ -330,59 +331,184 @@ __device__ __forceinline__ bool diff(const uint32_t (&a)[NW], const uint32_t (&b
     return any != 0;
 }
 
-// Bit-sliced sum over the rows of all active neurons: pl[p] holds digit p of
-// sum_j v_j w_ji for the 32 neurons of each word.  Returns the number of active neurons.
-template <int NW>
+// Bit-sliced counting.  pl[q] holds binary digit q of a per-neuron counter, 32 neurons per word.
+// full adder / half adder on bit vectors
+// (outputs may alias inputs)
+#define GBNN_FA(a, b, c, s, cy)                                        \
+    {                                                                  \
+        const uint32_t a_ = (a), b_ = (b), c_ = (c), t_ = a_ ^ b_;     \
+        s = t_ ^ c_;                                                   \
+        cy = (a_ & b_) | (c_ & t_);                                    \
+    }
+#define GBNN_HA(a, b, s, cy)                  \
+    {                                         \
+        const uint32_t a_ = (a), b_ = (b);    \
+        s = a_ ^ b_;                          \
+        cy = a_ & b_;                         \
+    }
+
+// pl += number of rows among r[0..B-1] that have the bit, for every bit position.  The B one-bit
+// rows are first compressed to one small binary number with a carry-save tree, then that number is
+// rippled into the counters; np = digits the counters can need afterwards.
+template <int NW, int B>
+__device__ __forceinline__ void add_rows(uint32_t (&pl)[kPlanes][NW], const uint32_t (&r)[B][NW], int np)
+{
+    static_assert(B == 4 || B == 8, "batch of 4 or 8 rows");
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+        uint32_t b[4];
+        int nb;
+        if (B == 8) {
+            uint32_t s0, c0, s1, c1, s2, c2, c3, s4, c4, c5;
+            GBNN_FA(r[0][u], r[1][u], r[2][u], s0, c0);
+            GBNN_FA(r[3][u], r[4][u], r[5][u], s1, c1);
+            GBNN_HA(r[6][u], r[7][u], s2, c2);
+            GBNN_FA(s0, s1, s2, b[0], c3);
+            GBNN_FA(c0, c1, c2, s4, c4);
+            GBNN_HA(c3, s4, b[1], c5);
+            GBNN_HA(c4, c5, b[2], b[3]);
+            nb = 4;
+        } else {
+            uint32_t s0, c0, c1;
+            GBNN_FA(r[0][u], r[1][u], r[2][u], s0, c0);
+            GBNN_HA(s0, r[3][u], b[0], c1);
+            GBNN_HA(c0, c1, b[1], b[2]);
+            b[3] = 0u;
+            nb = 3;
+        }
+        uint32_t cy = 0u;
+#pragma unroll
+        for (int q = 0; q < kPlanes; ++q) {
+            if (q < nb) {
+                GBNN_FA(pl[q][u], b[q], cy, pl[q][u], cy);
+            } else {
+                if (q >= np) break;
+                GBNN_HA(pl[q][u], cy, pl[q][u], cy);
+            }
+        }
+    }
+}
+
+// Bit-sliced sum over the rows of all active neurons: afterwards pl[q] holds digit q of
+//   sum_j v_j w_ji  +  (number of active neurons in i's own cluster)
+// for the 32 neurons i of each word: the rows are read from the table whose intra-cluster blocks
+// are all ones.  The second term is the same for all neurons of a cluster, so it changes neither
+// which neurons reach their cluster's maximum (Eq. 4-5) nor the count of a neuron in a cluster
+// without active neurons (the erased clusters of Algorithm 2).  Returns the number of active neurons.
+template <int NW, int LG>
 __device__ __forceinline__ int count_signals(const Ctx<NW> &x, const uint32_t (&v)[NW], uint32_t (&pl)[kPlanes][NW])
 {
 #pragma unroll
-    for (int p = 0; p < kPlanes; ++p)
+    for (int q = 0; q < kPlanes; ++q)
 #pragma unroll
-        for (int u = 0; u < NW; ++u) pl[p][u] = 0u;
-    int rows = 0;
+        for (int u = 0; u < NW; ++u) pl[q][u] = 0u;
+    uint32_t pw[NW];
+    uint64_t summask[NW];
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
-        uint64_t lanes = ballot(v[t] != 0u);
-        while (lanes) {
-            const int sl = __builtin_ctzll(lanes);
-            lanes &= lanes - 1;
-            uint32_t word = readlane(v[t], sl);
-            while (word) {
-                const uint32_t j = ((uint32_t)(t << 6 | sl) << 5) + (uint32_t)__builtin_ctz(word);
-                word &= word - 1;
-                uint32_t carry[NW];
-                load_row(x, x.wrsrc, j * x.rowbytes, carry);
-                ++rows;
-                const int np = 32 - __builtin_clz((unsigned)rows);  // digits a count of `rows` can need
+        pw[t] = v[t];
+        summask[t] = 0;
+    }
+    int rows = 0;
+    for (;;) {
+        uint32_t list;
+        const int total = take_chunk(x, pw, summask, list);
+        if (total == 0) break;
+        // lanes past the end point at the all-zero row of the table
+        const uint32_t jv = (x.lane < total) ? list - 1u : x.nrows + x.nclusters;
+        const uint32_t offv = __umul24(jv, x.rowbytes);
+        int i0 = 0;
+        while (i0 < total) {
+            if (total - i0 > 4) {
+                uint32_t r[8][NW];
 #pragma unroll
-                for (int p = 0; p < kPlanes; ++p) {
-                    if (p >= np) break;
+                for (int q = 0; q < 8; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+                i0 += 8;
+                const int upto = rows + (i0 < total ? i0 : total);
+                add_rows<NW, 8>(pl, r, 32 - __builtin_clz((unsigned)upto));
+            } else {
+                uint32_t r[4][NW];
 #pragma unroll
-                    for (int u = 0; u < NW; ++u) {
-                        const uint32_t c2 = pl[p][u] & carry[u];
-                        pl[p][u] ^= carry[u];
-                        carry[u] = c2;
-                    }
-                }
+                for (int q = 0; q < 4; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+                i0 += 4;
+                add_rows<NW, 4>(pl, r, 32 - __builtin_clz((unsigned)(rows + total)));
             }
         }
+        rows += total;
     }
     return rows;
 }
 
+// eq = neurons whose count of signals (rows of the active neurons of v having their bit) is exactly
+// `target` (< 128).  A 7-digit counter with a sticky overflow flag: enough to decide equality, and
+// few registers.  Used by the hybrid for probes outside the one-neuron-per-known-cluster contract.
+template <int NW, int LG>
+__device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (&v)[NW], int target, uint32_t (&eq)[NW])
+{
+    constexpr int D = 7;
+    uint32_t pl[D][NW], ovf[NW];
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+        ovf[u] = 0u;
+#pragma unroll
+        for (int q = 0; q < D; ++q) pl[q][u] = 0u;
+    }
+    uint32_t pw[NW];
+    uint64_t summask[NW];
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        pw[t] = v[t];
+        summask[t] = 0;
+    }
+    for (;;) {
+        uint32_t list;
+        const int total = take_chunk(x, pw, summask, list);
+        if (total == 0) break;
+        const uint32_t jv = (x.lane < total) ? list - 1u : x.nrows + x.nclusters;  // padding: the all-zero row
+        const uint32_t offv = __umul24(jv, x.rowbytes);
+        for (int i0 = 0; i0 < total; i0 += 4) {
+            uint32_t r[4][NW];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int u = 0; u < NW; ++u) {
+                    uint32_t carry = r[q][u];
+#pragma unroll
+                    for (int p = 0; p < D; ++p) {
+                        const uint32_t c2 = pl[p][u] & carry;
+                        pl[p][u] ^= carry;
+                        carry = c2;
+                    }
+                    ovf[u] |= carry;
+                }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+        uint32_t e = ~ovf[u];
+#pragma unroll
+        for (int p = 0; p < D; ++p) e &= ((target >> p) & 1) ? pl[p][u] : ~pl[p][u];
+        eq[u] = e;
+    }
+}
+
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
+// Register budget: the two row-AND rules are held to 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per
+// lane; sum-of-sum, with its 16 counter digits in registers, takes what it needs.
 template <int NW, int RULE, int LG>
-__global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RULE == GBNN_SUM_OF_SUM ? 1 : NW == 1 ? 8 : NW == 2 ? 5 : 4))) void
+k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
     constexpr int CPS = 64 / LW;  // clusters per slot
     Ctx<NW> x;
     x.rowbytes = (uint32_t)a.nw * 4u;
     x.nrows = (uint32_t)a.n;
-    x.wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.W), 0, (int)((uint32_t)a.n * x.rowbytes),
-                                                0x00020000);
+    x.nclusters = (uint32_t)a.C;
     x.wbrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
-                                                 (int)((uint32_t)(a.n + a.C) * x.rowbytes), 0x00020000);
+                                                 (int)((uint32_t)(a.n + a.C + 1) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
@@ -462,19 +588,12 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a)
                         d[t] = erased[t] ? 1u : 0u;  // known clusters have just been applied: clean
                     }
                 } else {
-                    // General probe: count the signals with bit-sliced counters, keep "== C - e".
-                    uint32_t pl[kPlanes][NW];
-                    const int rows = count_signals(x, v, pl);
-                    const int np = rows ? 32 - __builtin_clz((unsigned)rows) : 0;
+                    // General probe: count the signals, keep the erased-cluster neurons with exactly C - e.
+                    uint32_t eq[NW];
+                    signals_equal<NW, LG>(x, v, known, eq);
 #pragma unroll
                     for (int u = 0; u < NW; ++u) {
-                        uint32_t eq = 0xFFFFFFFFu;
-#pragma unroll
-                        for (int q = 0; q < kPlanes; ++q) {
-                            if (q >= np) break;
-                            eq &= ((known >> q) & 1) ? pl[q][u] : ~pl[q][u];
-                        }
-                        acc[u] = erased[u] ? eq : v[u];
+                        acc[u] = erased[u] ? eq[u] : v[u];
                         d[u] = x.valid[u] ? 1u : 0u;
                     }
                 }
@@ -499,7 +618,7 @@ __global__ __launch_bounds__(256) void k_retrieve_wave(RetrieveArgs a)
             int p = 0;
             for (;;) {
                 uint32_t pl[kPlanes][NW];
-                const int rows = count_signals(x, v, pl);
+                const int rows = count_signals<NW, LG>(x, v, pl);
                 const unsigned top = (unsigned)(rows + a.gamma);
                 const int P = top ? 32 - __builtin_clz(top) : 0;
                 if (a.gamma) {  // s_i += gamma * v_i : ripple add of a constant into the active neurons

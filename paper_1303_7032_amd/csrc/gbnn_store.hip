@@ -76,10 +76,12 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
 }
 
 // Wb = W with the intra-cluster blocks set to all ones: row j gets the bits of j's own cluster.
+// Also clears the all-zero row `zero_row` of the table.
 __global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict__ W, int L, int nw, int64_t words,
-                                                     uint32_t *__restrict__ Wb)
+                                                     uint32_t *__restrict__ Wb, uint32_t *__restrict__ zero_row)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nw; t += stride) zero_row[t] = 0u;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < words; t += stride) {
         const int j = (int)(t / nw);
         const int w = (int)(t - (int64_t)j * nw);
@@ -109,7 +111,8 @@ hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has
     const int64_t words = (int64_t)C * L * nw;
     int64_t blocks = (words + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_fill_blocks, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, words, Wb);
+    hipLaunchKernelGGL(k_fill_blocks, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, words, Wb,
+                       Wb + ((int64_t)C * L + C) * nw);
     return hipGetLastError();
 }
 
