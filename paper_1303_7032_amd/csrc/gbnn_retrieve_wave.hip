@@ -33,6 +33,7 @@ namespace gbnn {
 namespace {
 
 constexpr int kPlanes = 16;   // binary digits of a score: n + gamma < 2^16 by the interface limits
+constexpr int kRegPlanes = 8; // ... of which the low ones live in registers, the rest (scores >= 256) in LDS
 constexpr int kListMax = 56;  // entries of the in-register row list (batches of 8 stay below lane 64;
                               // lane 63 takes the idle pushes)
 
@@ -347,13 +348,50 @@ __device__ __forceinline__ bool diff(const uint32_t (&a)[NW], const uint32_t (&b
         cy = a_ & b_;                         \
     }
 
+// Bit-sliced counters of one probe: digit q of the counter of the 32 neurons of word (slot u, this
+// lane).  Digits 0..7 are registers; digits 8..15 are needed only when a score reaches 256 (hundreds
+// of active neurons, or a large gamma) and live in this wave's LDS column, zero until first written.
+template <int NW>
+struct Planes {
+    uint32_t lo[kRegPlanes][NW];
+    uint32_t *hi;  // LDS, [kPlanes - kRegPlanes][NW][64], this lane's column
+    int nhi;       // high digits written so far
+
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int q = 0; q < kRegPlanes; ++q)
+#pragma unroll
+            for (int u = 0; u < NW; ++u) lo[q][u] = 0u;
+        nhi = 0;
+    }
+    __device__ __forceinline__ uint32_t get_hi(int q, int u) const
+    {
+        return (q - kRegPlanes < nhi) ? hi[((q - kRegPlanes) * NW + u) * 64] : 0u;
+    }
+    __device__ __forceinline__ void set_hi(int q, int u, uint32_t val) { hi[((q - kRegPlanes) * NW + u) * 64] = val; }
+    // digits kRegPlanes..np-1 += carry-in cy[u] (half-adder ripple); afterwards np digits are valid
+    __device__ __forceinline__ void ripple_hi(uint32_t (&cy)[NW], int np)
+    {
+        for (int q = kRegPlanes; q < np; ++q)
+#pragma unroll
+            for (int u = 0; u < NW; ++u) {
+                const uint32_t dgt = get_hi(q, u);
+                set_hi(q, u, dgt ^ cy[u]);
+                cy[u] &= dgt;
+            }
+        if (np - kRegPlanes > nhi) nhi = np - kRegPlanes;
+    }
+};
+
 // pl += number of rows among r[0..B-1] that have the bit, for every bit position.  The B one-bit
 // rows are first compressed to one small binary number with a carry-save tree, then that number is
 // rippled into the counters; np = digits the counters can need afterwards.
 template <int NW, int B>
-__device__ __forceinline__ void add_rows(uint32_t (&pl)[kPlanes][NW], const uint32_t (&r)[B][NW], int np)
+__device__ __forceinline__ void add_rows(Planes<NW> &pl, const uint32_t (&r)[B][NW], int np)
 {
     static_assert(B == 4 || B == 8, "batch of 4 or 8 rows");
+    uint32_t cyv[NW];
 #pragma unroll
     for (int u = 0; u < NW; ++u) {
         uint32_t b[4];
@@ -378,30 +416,28 @@ __device__ __forceinline__ void add_rows(uint32_t (&pl)[kPlanes][NW], const uint
         }
         uint32_t cy = 0u;
 #pragma unroll
-        for (int q = 0; q < kPlanes; ++q) {
+        for (int q = 0; q < kRegPlanes; ++q) {
             if (q < nb) {
-                GBNN_FA(pl[q][u], b[q], cy, pl[q][u], cy);
+                GBNN_FA(pl.lo[q][u], b[q], cy, pl.lo[q][u], cy);
             } else {
                 if (q >= np) break;
-                GBNN_HA(pl[q][u], cy, pl[q][u], cy);
+                GBNN_HA(pl.lo[q][u], cy, pl.lo[q][u], cy);
             }
         }
+        cyv[u] = cy;
     }
+    if (np > kRegPlanes) pl.ripple_hi(cyv, np);
 }
 
-// Bit-sliced sum over the rows of all active neurons: afterwards pl[q] holds digit q of
+// Bit-sliced sum over the rows of all active neurons: afterwards digit q of
 //   sum_j v_j w_ji  +  (number of active neurons in i's own cluster)
 // for the 32 neurons i of each word: the rows are read from the table whose intra-cluster blocks
-// are all ones.  The second term is the same for all neurons of a cluster, so it changes neither
-// which neurons reach their cluster's maximum (Eq. 4-5) nor the count of a neuron in a cluster
-// without active neurons (the erased clusters of Algorithm 2).  Returns the number of active neurons.
+// are all ones.  The second term is the same for all neurons of a cluster, so it does not change
+// which neurons reach their cluster's maximum (Eq. 4-5).  Returns the number of active neurons.
 template <int NW, int LG>
-__device__ __forceinline__ int count_signals(const Ctx<NW> &x, const uint32_t (&v)[NW], uint32_t (&pl)[kPlanes][NW])
+__device__ __forceinline__ int count_signals(const Ctx<NW> &x, const uint32_t (&v)[NW], Planes<NW> &pl)
 {
-#pragma unroll
-    for (int q = 0; q < kPlanes; ++q)
-#pragma unroll
-        for (int u = 0; u < NW; ++u) pl[q][u] = 0u;
+    pl.clear();
     uint32_t pw[NW];
     uint64_t summask[NW];
 #pragma unroll
@@ -495,14 +531,15 @@ __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (
 }
 
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
-// Register budget: the two row-AND rules are held to 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per
-// lane; sum-of-sum, with its 16 counter digits in registers, takes what it needs.
+// Register budget: 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per lane (2 for sum-of-sum at 4).
 template <int NW, int RULE, int LG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RULE == GBNN_SUM_OF_SUM ? 1 : NW == 1 ? 8 : NW == 2 ? 5 : 4))) void
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? 5 : RULE == GBNN_SUM_OF_SUM ? 2 : 4))) void
 k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
     constexpr int CPS = 64 / LW;  // clusters per slot
+    // high counter digits of sum-of-sum, one column per lane and wave (unused by the other rules)
+    __shared__ uint32_t sos_hi[RULE == GBNN_SUM_OF_SUM ? 4 * (kPlanes - kRegPlanes) * NW * 64 : 1];
     Ctx<NW> x;
     x.rowbytes = (uint32_t)a.nw * 4u;
     x.nrows = (uint32_t)a.n;
@@ -615,36 +652,52 @@ k_retrieve_wave(RetrieveArgs a)
             }
         } else {
             // Algorithm 1 with Eq. (3)-(5).
+            Planes<NW> pl;
+            pl.hi = sos_hi + (threadIdx.x >> 6) * ((kPlanes - kRegPlanes) * NW * 64) + x.lane;
             int p = 0;
             for (;;) {
-                uint32_t pl[kPlanes][NW];
                 const int rows = count_signals<NW, LG>(x, v, pl);
                 const unsigned top = (unsigned)(rows + a.gamma);
                 const int P = top ? 32 - __builtin_clz(top) : 0;
                 if (a.gamma) {  // s_i += gamma * v_i : ripple add of a constant into the active neurons
+                    uint32_t cy[NW];
 #pragma unroll
                     for (int u = 0; u < NW; ++u) {
-                        uint32_t cy = 0u;
+                        cy[u] = 0u;
 #pragma unroll
-                        for (int q = 0; q < kPlanes; ++q) {
+                        for (int q = 0; q < kRegPlanes; ++q) {
                             if (q >= P) break;
                             const uint32_t g = ((a.gamma >> q) & 1) ? v[u] : 0u;
-                            const uint32_t dg = pl[q][u];
-                            pl[q][u] = dg ^ g ^ cy;
-                            cy = (dg & g) | (cy & (dg ^ g));
+                            GBNN_FA(pl.lo[q][u], g, cy[u], pl.lo[q][u], cy[u]);
                         }
                     }
+                    for (int q = kRegPlanes; q < P; ++q)
+#pragma unroll
+                        for (int u = 0; u < NW; ++u) {
+                            const uint32_t g = ((a.gamma >> q) & 1) ? v[u] : 0u;
+                            uint32_t sum;
+                            GBNN_FA(pl.get_hi(q, u), g, cy[u], sum, cy[u]);
+                            pl.set_hi(q, u, sum);
+                        }
+                    if (P - kRegPlanes > pl.nhi) pl.nhi = P - kRegPlanes;
                 }
-                // Eq. (4)-(5): per cluster keep the neurons whose score is the cluster maximum.
+                // Eq. (4)-(5): per cluster keep the neurons whose score is the cluster maximum,
+                // found digit by digit from the top.
                 uint32_t cand[NW];
 #pragma unroll
                 for (int u = 0; u < NW; ++u) cand[u] = x.valid[u] ? 0xFFFFFFFFu : 0u;
+                for (int q = P - 1; q >= kRegPlanes; --q)
 #pragma unroll
-                for (int q = kPlanes - 1; q >= 0; --q) {
+                    for (int u = 0; u < NW; ++u) {
+                        const uint32_t tt = cand[u] & pl.get_hi(q, u);
+                        if (group_or<LG>(tt) != 0u) cand[u] = tt;
+                    }
+#pragma unroll
+                for (int q = kRegPlanes - 1; q >= 0; --q) {
                     if (q >= P) continue;
 #pragma unroll
                     for (int u = 0; u < NW; ++u) {
-                        const uint32_t tt = cand[u] & pl[q][u];
+                        const uint32_t tt = cand[u] & pl.lo[q][u];
                         if (group_or<LG>(tt) != 0u) cand[u] = tt;
                     }
                 }

@@ -184,7 +184,7 @@ def test_arbitrary_binary_probes(networks, C, L, M, rule):
     v[: L // 2] = 0
     rows.append(v)
     V0 = np.stack(rows)
-    for gamma, cap in ((1, 6), (0, 4), (5, 4)):
+    for gamma, cap in ((1, 6), (0, 4), (5, 4), (300, 3), (32767, 3)):  # scores beyond 8 and 15 binary digits too
         ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
         out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap)
         check_same(out, it, ref, itref, f"{rule} gamma={gamma}")
