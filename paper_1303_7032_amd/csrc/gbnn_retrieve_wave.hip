@@ -15,7 +15,7 @@
 //     pass cannot switch anything off, so only "dirty" clusters are walked.
 //   sum-of-sum (Eq. 3-5): the rows are added into bit-sliced counters (one register per binary
 //     digit of the score), gamma is added to active neurons, and the per-cluster maximum is
-//     found digit by digit from the top with a ballot per digit.
+//     found digit by digit from the top with a cluster-wide OR per digit.
 //   hybrid (Algorithm 2): pass 1 keeps the erased-cluster neurons with exactly C - e signals: the
 //     AND of the known neurons' rows when each known cluster holds one active neuron, the counter
 //     form otherwise; later passes are the sum-of-max update applied to erased clusters only.
