@@ -120,7 +120,8 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
 const char *gbnn_strerror(int code);
 
 /* Name of the kernel family gbnn_retrieve would run for this shape, rule and pointer alignment
- * ("wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
+ * ("half1" = two probes per wavefront, one packed word per lane, networks of up to 1024 neurons;
+ * "wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
  * "generic" = any shape), or NULL for invalid arguments.  Host only; for tests and reports. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
 

@@ -18,12 +18,19 @@ bool rule_ok(int rule) { return rule == GBNN_SUM_OF_SUM || rule == GBNN_SUM_OF_M
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-// Words per lane of the one-wave-per-probe kernel, or 0 for the any-shape kernel.
+// Kernel family for a call: 0 = any-shape kernel; 1, 2, 4 = one wavefront per probe with that many packed
+// words per lane; kHalfPath = half a wavefront per probe.  The environment variables GBNN_FORCE_GENERIC=1
+// and GBNN_FORCE_WAVE=1 (no half-wave kernel) exist for tests and A/B timing.
+constexpr int kHalfPath = 10;
 int pick_path(int C, int L, const void *V0, const void *Vout)
 {
     const char *force = std::getenv("GBNN_FORCE_GENERIC");
     if (force && force[0] == '1') return 0;
     if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;
+    const char *wave = std::getenv("GBNN_FORCE_WAVE");
+    if (!(wave && wave[0] == '1')) {
+        if (half_wave_serves(C, L)) return kHalfPath;
+    }
     return wave_words_per_lane(C, L);
 }
 
@@ -102,8 +109,10 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
     a.gamma = gamma;
     a.max_iters = max_iters;
 
-    const int wpl = pick_path(C, L, V0, V_out);
-    const hipError_t e = wpl ? launch_retrieve_wave(a, wpl, s) : launch_retrieve_generic(a, s);
+    const int path = pick_path(C, L, V0, V_out);
+    const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
+                         : path            ? launch_retrieve_wave(a, path, s)
+                                           : launch_retrieve_generic(a, s);
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
@@ -129,6 +138,7 @@ const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const voi
     case 1: return "wave1";
     case 2: return "wave2";
     case 4: return "wave4";
+    case kHalfPath: return "half1";
     default: return "generic";
     }
 }

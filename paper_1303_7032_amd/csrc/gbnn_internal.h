@@ -23,22 +23,27 @@ struct RetrieveArgs {
     int rule, gamma, max_iters;
 };
 
-// Workspace layout: one table of n + C + 1 rows of nw words.  Rows 0..n-1: W with all-one intra-cluster
-// blocks; rows n..n+C-1: the cluster summaries; row n+C: all zero (what the padding entries of a batch of
-// row fetches read when rows are counted).  One table, so that one buffer resource reaches all of it.
+// Workspace layout: one table of n + C + 2 rows of nw words.  Rows 0..n-1: W with all-one intra-cluster
+// blocks; rows n..n+C-1: the cluster summaries; row n+C: all zero and row n+C+1: all ones (what the
+// padding entries of a batch of row fetches read when rows are counted, resp. ANDed).  One table, so
+// that one buffer resource reaches all of it.
+constexpr int kTableExtraRows = 2;  // the all-zero and the all-one row
 inline size_t workspace_has_offset(int C, int L, int nw) { return (size_t)C * L * nw * sizeof(uint32_t); }
 inline size_t workspace_total_bytes(int C, int L, int nw)
 {
-    return (((size_t)C * L + C + 1) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
+    return (((size_t)C * L + C + kTableExtraRows) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
 
-// Which kernel family serves a shape: 0 = generic, otherwise packed words per lane (1, 2, 4).
+// Which kernel family serves a shape.  One wavefront per probe: packed words per lane (1, 2, 4), 0 = not
+// served.  Half a wavefront per probe (two probes per wave, one word per lane): yes or no.
 int wave_words_per_lane(int C, int L);
+bool half_wave_serves(int C, int L);
 
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
                         hipStream_t s);
 hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, hipStream_t s);
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);
+hipError_t launch_retrieve_half(const RetrieveArgs &a, hipStream_t s);
 hipError_t launch_retrieve_generic(const RetrieveArgs &a, hipStream_t s);
 
 }  // namespace gbnn

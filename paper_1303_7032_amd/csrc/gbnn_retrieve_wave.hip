@@ -27,43 +27,14 @@
 // v_readlane plus one buffer_load (row offset in the scalar-offset operand) per row.
 #include <cstdlib>
 
+#include "gbnn_device.h"
 #include "gbnn_internal.h"
 
 namespace gbnn {
 namespace {
 
-constexpr int kPlanes = 16;   // binary digits of a score: n + gamma < 2^16 by the interface limits
-constexpr int kRegPlanes = 8; // ... of which the low ones live in registers, the rest (scores >= 256) in LDS
 constexpr int kListMax = 56;  // entries of the in-register row list (batches of 8 stay below lane 64;
                               // lane 63 takes the idle pushes)
-
-__device__ __forceinline__ uint32_t readlane(uint32_t x, int l)
-{
-    return (uint32_t)__builtin_amdgcn_readlane((int)x, l);
-}
-__device__ __forceinline__ uint64_t ballot(bool p) { return (uint64_t)__ballot(p); }
-// Number of set bits of the wave-uniform mask m in lanes below this one.
-__device__ __forceinline__ uint32_t mbcnt(uint64_t m)
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-
-// 16 activity bytes (each 0 or 1) -> 16 bits, byte k -> bit k: byte-wise dot products with the
-// weights 1,2,4,8 / 16,32,64,128 (v_dot4_u32_u8 accumulates), two bytes of result glued together.
-__device__ __forceinline__ uint32_t pack16(uint4 a)
-{
-    uint32_t lo = __builtin_amdgcn_udot4(a.x, 0x08040201u, 0u, false);
-    lo = __builtin_amdgcn_udot4(a.y, 0x80402010u, lo, false);
-    uint32_t hi = __builtin_amdgcn_udot4(a.z, 0x08040201u, 0u, false);
-    hi = __builtin_amdgcn_udot4(a.w, 0x80402010u, hi, false);
-    return lo | (hi << 8);
-}
-// 4 bits -> 4 bytes of 0/1.
-__device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
-__device__ __forceinline__ uint4 spread16(uint32_t h)
-{
-    return make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4((h >> 12) & 15u));
-}
 
 template <int NW>
 struct Ctx {
@@ -90,28 +61,6 @@ __device__ __forceinline__ void load_row(const Ctx<NW> &x, __amdgpu_buffer_rsrc_
 {
 #pragma unroll
     for (int u = 0; u < NW; ++u) r[u] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, x.woffb[u], rowoff, 0);
-}
-
-// A wave-uniform lane mask read as a per-lane flag (no vector arithmetic: the mask is the condition).
-__device__ __forceinline__ bool lane_of(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
-
-// OR over the 2^LG lanes of this lane's group (a group = the lanes holding one cluster), left in
-// every lane of the group: a butterfly of DPP moves inside a row of 16 lanes, ds_bpermute beyond.
-template <int CTRL>
-__device__ __forceinline__ uint32_t or_dpp(uint32_t v)
-{
-    return v | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
-}
-template <int LG>
-__device__ __forceinline__ uint32_t group_or(uint32_t v)
-{
-    if (LG >= 1) v = or_dpp<0xB1>(v);   // quad_perm [1,0,3,2]
-    if (LG >= 2) v = or_dpp<0x4E>(v);   // quad_perm [2,3,0,1]
-    if (LG >= 3) v = or_dpp<0x141>(v);  // row_half_mirror
-    if (LG >= 4) v = or_dpp<0x140>(v);  // row_mirror
-    if (LG >= 5) v |= (uint32_t)__shfl_xor((int)v, 16);
-    if (LG >= 6) v |= (uint32_t)__shfl_xor((int)v, 32);
-    return v;
 }
 
 // Does some existing group of slot t have no set bit in the lane mask m?  (The zero-field test
@@ -332,103 +281,6 @@ __device__ __forceinline__ bool diff(const uint32_t (&a)[NW], const uint32_t (&b
     return any != 0;
 }
 
-// Bit-sliced counting.  pl[q] holds binary digit q of a per-neuron counter, 32 neurons per word.
-// full adder / half adder on bit vectors
-// (outputs may alias inputs)
-#define GBNN_FA(a, b, c, s, cy)                                        \
-    {                                                                  \
-        const uint32_t a_ = (a), b_ = (b), c_ = (c), t_ = a_ ^ b_;     \
-        s = t_ ^ c_;                                                   \
-        cy = (a_ & b_) | (c_ & t_);                                    \
-    }
-#define GBNN_HA(a, b, s, cy)                  \
-    {                                         \
-        const uint32_t a_ = (a), b_ = (b);    \
-        s = a_ ^ b_;                          \
-        cy = a_ & b_;                         \
-    }
-
-// Bit-sliced counters of one probe: digit q of the counter of the 32 neurons of word (slot u, this
-// lane).  Digits 0..7 are registers; digits 8..15 are needed only when a score reaches 256 (hundreds
-// of active neurons, or a large gamma) and live in this wave's LDS column, zero until first written.
-template <int NW>
-struct Planes {
-    uint32_t lo[kRegPlanes][NW];
-    uint32_t *hi;  // LDS, [kPlanes - kRegPlanes][NW][64], this lane's column
-    int nhi;       // high digits written so far
-
-    __device__ __forceinline__ void clear()
-    {
-#pragma unroll
-        for (int q = 0; q < kRegPlanes; ++q)
-#pragma unroll
-            for (int u = 0; u < NW; ++u) lo[q][u] = 0u;
-        nhi = 0;
-    }
-    __device__ __forceinline__ uint32_t get_hi(int q, int u) const
-    {
-        return (q - kRegPlanes < nhi) ? hi[((q - kRegPlanes) * NW + u) * 64] : 0u;
-    }
-    __device__ __forceinline__ void set_hi(int q, int u, uint32_t val) { hi[((q - kRegPlanes) * NW + u) * 64] = val; }
-    // digits kRegPlanes..np-1 += carry-in cy[u] (half-adder ripple); afterwards np digits are valid
-    __device__ __forceinline__ void ripple_hi(uint32_t (&cy)[NW], int np)
-    {
-        for (int q = kRegPlanes; q < np; ++q)
-#pragma unroll
-            for (int u = 0; u < NW; ++u) {
-                const uint32_t dgt = get_hi(q, u);
-                set_hi(q, u, dgt ^ cy[u]);
-                cy[u] &= dgt;
-            }
-        if (np - kRegPlanes > nhi) nhi = np - kRegPlanes;
-    }
-};
-
-// pl += number of rows among r[0..B-1] that have the bit, for every bit position.  The B one-bit
-// rows are first compressed to one small binary number with a carry-save tree, then that number is
-// rippled into the counters; np = digits the counters can need afterwards.
-template <int NW, int B>
-__device__ __forceinline__ void add_rows(Planes<NW> &pl, const uint32_t (&r)[B][NW], int np)
-{
-    static_assert(B == 4 || B == 8, "batch of 4 or 8 rows");
-    uint32_t cyv[NW];
-#pragma unroll
-    for (int u = 0; u < NW; ++u) {
-        uint32_t b[4];
-        int nb;
-        if (B == 8) {
-            uint32_t s0, c0, s1, c1, s2, c2, c3, s4, c4, c5;
-            GBNN_FA(r[0][u], r[1][u], r[2][u], s0, c0);
-            GBNN_FA(r[3][u], r[4][u], r[5][u], s1, c1);
-            GBNN_HA(r[6][u], r[7][u], s2, c2);
-            GBNN_FA(s0, s1, s2, b[0], c3);
-            GBNN_FA(c0, c1, c2, s4, c4);
-            GBNN_HA(c3, s4, b[1], c5);
-            GBNN_HA(c4, c5, b[2], b[3]);
-            nb = 4;
-        } else {
-            uint32_t s0, c0, c1;
-            GBNN_FA(r[0][u], r[1][u], r[2][u], s0, c0);
-            GBNN_HA(s0, r[3][u], b[0], c1);
-            GBNN_HA(c0, c1, b[1], b[2]);
-            b[3] = 0u;
-            nb = 3;
-        }
-        uint32_t cy = 0u;
-#pragma unroll
-        for (int q = 0; q < kRegPlanes; ++q) {
-            if (q < nb) {
-                GBNN_FA(pl.lo[q][u], b[q], cy, pl.lo[q][u], cy);
-            } else {
-                if (q >= np) break;
-                GBNN_HA(pl.lo[q][u], cy, pl.lo[q][u], cy);
-            }
-        }
-        cyv[u] = cy;
-    }
-    if (np > kRegPlanes) pl.ripple_hi(cyv, np);
-}
-
 // Bit-sliced sum over the rows of all active neurons: afterwards digit q of
 //   sum_j v_j w_ji  +  (number of active neurons in i's own cluster)
 // for the 32 neurons i of each word: the rows are read from the table whose intra-cluster blocks
@@ -545,7 +397,7 @@ k_retrieve_wave(RetrieveArgs a)
     x.nrows = (uint32_t)a.n;
     x.nclusters = (uint32_t)a.C;
     x.wbrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
-                                                 (int)((uint32_t)(a.n + a.C + 1) * x.rowbytes), 0x00020000);
+                                                 (int)((uint32_t)(a.n + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
 #pragma unroll
     for (int t = 0; t < NW; ++t) {

@@ -76,12 +76,15 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
 }
 
 // Wb = W with the intra-cluster blocks set to all ones: row j gets the bits of j's own cluster.
-// Also clears the all-zero row `zero_row` of the table.
+// Also fills the all-zero row `zero_row` of the table and the all-one row that follows it.
 __global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict__ W, int L, int nw, int64_t words,
                                                      uint32_t *__restrict__ Wb, uint32_t *__restrict__ zero_row)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nw; t += stride) zero_row[t] = 0u;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nw; t += stride) {
+        zero_row[t] = 0u;
+        zero_row[nw + t] = 0xFFFFFFFFu;
+    }
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < words; t += stride) {
         const int j = (int)(t / nw);
         const int w = (int)(t - (int64_t)j * nw);

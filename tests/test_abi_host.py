@@ -87,7 +87,10 @@ def test_strerror_and_path(lib):
         assert gb.gbnn_strerror(code)
     assert gb.gbnn_strerror(0) == "ok"
     assert gb.gbnn_retrieve_path(8, 256, "sum_of_max") == "wave1"
-    assert gb.gbnn_retrieve_path(8, 128, "sum_of_sum") == "wave1"
+    assert gb.gbnn_retrieve_path(8, 128, "sum_of_sum") == "half1"
+    assert gb.gbnn_retrieve_path(32, 32, "hybrid") == "half1"
+    assert gb.gbnn_retrieve_path(2, 512, "sum_of_max") == "half1"
+    assert gb.gbnn_retrieve_path(64, 32, "sum_of_max") == "wave1"
     assert gb.gbnn_retrieve_path(16, 512, "hybrid") == "wave4"
     assert gb.gbnn_retrieve_path(12, 256, "hybrid") == "wave2"
     assert gb.gbnn_retrieve_path(4, 16, "sum_of_max") == "generic"

@@ -32,19 +32,34 @@ def dev_store(C, L, msgs):
     return W, int(status.item())
 
 
-def dev_retrieve(W, C, L, V0, rule, gamma, cap, force_generic=False, **kw):
-    old = os.environ.get("GBNN_FORCE_GENERIC")
-    os.environ["GBNN_FORCE_GENERIC"] = "1" if force_generic else "0"
+def dev_retrieve(W, C, L, V0, rule, gamma, cap, force_generic=False, force_wave=False, **kw):
+    """gbnn_retrieve on the kernel family the library picks, or with the any-shape kernel forced, or
+    with the two-probes-per-wave kernel switched off (the library reads the environment per call)."""
+    want = {"GBNN_FORCE_GENERIC": "1" if force_generic else "0", "GBNN_FORCE_WAVE": "1" if force_wave else "0"}
+    old = {k: os.environ.get(k) for k in want}
+    os.environ.update(want)
     try:
         V0d = torch.from_numpy(V0).cuda() if isinstance(V0, np.ndarray) else V0
         out, it = gb.gbnn_retrieve(W, C, L, V0d, rule, gamma, cap, **kw)
         torch.cuda.synchronize()
     finally:
-        if old is None:
-            os.environ.pop("GBNN_FORCE_GENERIC", None)
-        else:
-            os.environ["GBNN_FORCE_GENERIC"] = old
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
     return out.cpu().numpy(), it.cpu().numpy()
+
+
+def other_paths(C, L, rule):
+    """Keyword sets that force every other kernel family able to serve the shape."""
+    path = gb.gbnn_retrieve_path(C, L, rule, torch.zeros(1, device="cuda"))
+    alts = []
+    if path.startswith("half"):
+        alts.append(("wave", {"force_wave": True}))
+    if path != "generic":
+        alts.append(("generic", {"force_generic": True}))
+    return alts
 
 
 def check_same(out, it, ref, itref, what):
@@ -118,6 +133,11 @@ SHAPES = [
     (16, 512, 100000, 8, 260),  # cfg5 shape: four words per lane
     (2, 2048, 3000, 1, 70),  # a cluster is a whole wave
     (16, 1024, 60000, 8, 20),  # n = 16384: the largest shape, any-shape kernel
+    (32, 32, 700, 16, 131),    # two probes per wave, a cluster is one lane, odd K
+    (16, 64, 800, 8, 130),     # ... two lanes per cluster
+    (2, 512, 30000, 1, 67),    # ... a cluster is half of the half-wave
+    (32, 64, 3000, 16, 131),   # 64 words, two per cluster: one wave per probe
+    (64, 32, 1000, 32, 45),    # 64 one-word clusters
 ]
 
 
@@ -147,15 +167,17 @@ def test_probes_from_stored_messages(networks, C, L, M, e, K, rule):
         ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
         out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap)
         check_same(out, it, ref, itref, f"{rule} gamma={gamma} cap={cap}")
-        if gb.gbnn_retrieve_path(C, L, rule, torch.zeros(1, device="cuda")) != "generic" and K <= 300:
-            out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, force_generic=True)
-            check_same(out, it, ref, itref, f"{rule} generic gamma={gamma} cap={cap}")
+        for nm, kw in other_paths(C, L, rule):
+            if nm == "generic" and K > 300:
+                continue
+            out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, **kw)
+            check_same(out, it, ref, itref, f"{rule} {nm} gamma={gamma} cap={cap}")
         if rule != "sum_of_sum":
             break  # gamma is ignored by the other rules
 
 
 @pytest.mark.parametrize("C,L,M", [(4, 16, 50), (5, 12, 200), (8, 32, 300), (8, 128, 5000), (8, 256, 20000),
-                                    (16, 512, 100000)])
+                                    (16, 512, 100000), (32, 32, 700), (2, 512, 30000)])
 @pytest.mark.parametrize("rule", RULES)
 def test_arbitrary_binary_probes(networks, C, L, M, rule):
     """Probes outside the one-active-neuron-per-cluster contract: several active neurons in a
@@ -188,8 +210,9 @@ def test_arbitrary_binary_probes(networks, C, L, M, rule):
         ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
         out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap)
         check_same(out, it, ref, itref, f"{rule} gamma={gamma}")
-        out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, force_generic=True)
-        check_same(out, it, ref, itref, f"{rule} generic gamma={gamma}")
+        for nm, kw in other_paths(C, L, rule):
+            out, it = dev_retrieve(Wd, C, L, V0, rule, gamma, cap, **kw)
+            check_same(out, it, ref, itref, f"{rule} {nm} gamma={gamma}")
         if rule != "sum_of_sum":
             break
 
@@ -209,6 +232,8 @@ def test_edge_cases(networks):
                 ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, 1, cap)
                 out, it = dev_retrieve(Wd, C, L, V0, rule, 1, cap)
                 check_same(out, it, ref, itref, f"e={e} {rule} cap={cap}")
+                out, it = dev_retrieve(Wd, C, L, V0, rule, 1, cap, force_wave=True)
+                check_same(out, it, ref, itref, f"e={e} {rule} cap={cap} wave")
     # in place, without iters_out; then through an unaligned view (any-shape kernel)
     q, er = inputs.make_probe_plan(C, M, 77, 4, 10)
     V0 = inputs.one_hot(msgs[q], L, er)
