@@ -158,3 +158,49 @@ def pack_bits(Wfull: np.ndarray) -> np.ndarray:
     padded[:, :n] = Wfull
     b = np.packbits(padded.reshape(n, nw, 32), axis=2, bitorder="little")  # [n][nw][4] bytes, LSB first
     return b.view("<u4").reshape(n, nw)
+
+
+# ------------------------------------------------------------------ symbols in, symbols / packed bits out
+SYM_NONE, SYM_AMBIGUOUS = -1, -2
+
+
+def encode_probes(C: int, L: int, probes: np.ndarray) -> np.ndarray:
+    """Partially erased messages -> activity vectors (Section II-A: a message activates the neuron
+    of its symbol in every cluster; an erased cluster has no active neuron).  probes is
+    int32[K][C] with 0-based symbols; any entry outside [0, L) (-1 by convention) marks the
+    cluster as erased.  Plain loops: this is the definition."""
+    probes = np.asarray(probes, dtype=np.int64).reshape(-1, C)
+    V = np.zeros((probes.shape[0], C * L), dtype=np.uint8)
+    for k in range(probes.shape[0]):
+        for c in range(C):
+            s = int(probes[k, c])
+            if 0 <= s < L:
+                V[k, c * L + s] = 1
+    return V
+
+
+def decode(C: int, L: int, V: np.ndarray):
+    """Activity vectors -> (packed bits uint32[K][ceil(n/32)], symbols int32[K][C]).  Bit i%32 of
+    word i//32 is neuron i, least significant bit first.  The symbol of a cluster is the index of
+    its active neuron if it has exactly one, SYM_NONE if it has none, SYM_AMBIGUOUS if it has
+    several (Section V-B: several cliques may survive)."""
+    V = np.asarray(V, dtype=np.uint8).reshape(-1, C * L)
+    K, n = V.shape
+    nw = (n + 31) // 32
+    bits = np.zeros((K, nw), dtype=np.uint32)
+    sym = np.zeros((K, C), dtype=np.int32)
+    for k in range(K):
+        for i in np.nonzero(V[k])[0]:
+            bits[k, i // 32] |= np.uint32(1) << np.uint32(i % 32)
+        for c in range(C):
+            on = np.nonzero(V[k, c * L:(c + 1) * L])[0]
+            sym[k, c] = int(on[0]) if len(on) == 1 else (SYM_NONE if len(on) == 0 else SYM_AMBIGUOUS)
+    return bits, sym
+
+
+def retrieve_symbols(W, C, L, probes, rule, gamma=1, max_iters=20, nthreads=0):
+    """The retrieval of `retrieve` with messages at the boundary: encode, retrieve, decode.
+    Returns (bits, symbols, iters)."""
+    out, iters, _ = retrieve(W, C, L, encode_probes(C, L, probes), rule, gamma, max_iters, nthreads)
+    bits, sym = decode(C, L, out)
+    return bits, sym, iters

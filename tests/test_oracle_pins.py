@@ -400,3 +400,50 @@ def test_pack_bits_layout():
     p = orc.pack_bits(Wf)
     assert p.shape == (40, 2) and p.dtype == np.dtype("<u4")
     assert p[3, 0] == 1 and p[3, 1] == 2 and p[39, 0] == 0x80000000
+
+
+# ------------------------------------------------------------------ messages at the boundary (symbols in / out)
+def test_encode_matches_the_printed_code_and_decode_inverts_it():
+    """Section II-A's worked example: message (9,4,3,10) (1-based) and its printed binary code."""
+    g = read_golden("encoding_example.txt")
+    C, L = int(g["C"][0]), int(g["L"][0])
+    msg = np.array([int(x) - 1 for x in g["message_1based"][0].split()], dtype=np.int32)
+    code = np.array([int(ch) for ch in "".join(g["code"][0].split())], dtype=np.uint8)
+    V = orc.encode_probes(C, L, msg[None, :])
+    assert (V[0] == code).all()
+    bits, sym = orc.decode(C, L, V)
+    assert (sym[0] == msg).all()
+    # packed bits: neuron i is bit i%32 of word i//32, LSB first -> compare with numpy's own packing
+    assert (bits[0] == np.packbits(code, bitorder="little").view("<u4")).all()
+
+
+def test_encode_erasures_and_decode_none_and_ambiguous():
+    C, L = 3, 5                                                  # n = 15: one padded word
+    V = orc.encode_probes(C, L, np.array([[4, -1, 0], [5, 2, -7]], dtype=np.int32))
+    assert V[0].tolist() == [0, 0, 0, 0, 1, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0]
+    assert V[1].tolist() == [0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0, 0, 0, 0]   # 5 and -7 are outside [0, L): erased
+    V[1, 10:13] = 1
+    bits, sym = orc.decode(C, L, V)
+    assert sym.tolist() == [[4, orc.SYM_NONE, 0], [orc.SYM_NONE, 2, orc.SYM_AMBIGUOUS]]
+    assert bits.shape == (2, 1) and bits[0, 0] == (1 << 4) | (1 << 10) and bits[1, 0] == (1 << 7) | (0b111 << 10)
+
+
+def test_retrieve_symbols_is_retrieve_on_the_one_hot_probe():
+    C, L, M = 4, 16, 50
+    msgs = inputs.make_messages(C, L, M, 3)
+    W, _ = orc.store(C, L, msgs)
+    q, er = inputs.make_probe_plan(C, M, 40, 2, 8)
+    probes = msgs[q].copy()
+    probes[er] = -1
+    V0 = inputs.one_hot(msgs[q], L, er)
+    assert (orc.encode_probes(C, L, probes) == V0).all()
+    for rule in ("sum_of_sum", "sum_of_max", "hybrid"):
+        ref, itref, _ = orc.retrieve(W, C, L, V0, rule, 1, 6)
+        bits, sym, it = orc.retrieve_symbols(W, C, L, probes, rule, 1, 6)
+        assert (it == itref).all()
+        for k in range(40):
+            act = ref[k].reshape(C, L)
+            for c in range(C):
+                cnt = int(act[c].sum())
+                assert sym[k, c] == (int(act[c].argmax()) if cnt == 1 else (-1 if cnt == 0 else -2))
+            assert [(int(bits[k, i // 32]) >> (i % 32)) & 1 for i in range(C * L)] == ref[k].tolist()
