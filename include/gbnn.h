@@ -116,13 +116,34 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
                   void *stream);
 
+/*
+ * The same retrieval with messages at the boundary (Section II-A: a message is C symbols, a probe is
+ * a message with some symbols erased): 4*C bytes in per probe instead of n, and the result as packed
+ * bits and / or symbols instead of n bytes.  Probe k is the activity vector with neuron
+ * c*L + probes[k][c] active for every cluster c whose entry lies in [0, L) and no active neuron in
+ * the other clusters (-1, by convention, marks an erased cluster); rule, gamma, max_iters,
+ * iters_out, workspace and errors are those of gbnn_retrieve, and so is the final activity vector.
+ *   probes       device, int32_t[K][C]
+ *   bits_out     device uint32_t[K][nw] or NULL: the final activity vector, neuron i = bit (i % 32)
+ *                of word (i / 32), least significant bit first, padding bits zero
+ *   symbols_out  device int32_t[K][C] or NULL: per cluster, the index of its active neuron if it
+ *                holds exactly one, GBNN_SYM_NONE if none, GBNN_SYM_AMBIGUOUS if several (more than
+ *                one clique survived, Section V-B)
+ */
+#define GBNN_SYM_NONE (-1)
+#define GBNN_SYM_AMBIGUOUS (-2)
+int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes, int64_t K, int rule, int gamma,
+                          int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 /* Static description of a status code (never NULL). */
 const char *gbnn_strerror(int code);
 
 /* Name of the kernel family gbnn_retrieve would run for this shape, rule and pointer alignment
  * ("half1" = two probes per wavefront, one packed word per lane, networks of up to 1024 neurons;
  * "wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
- * "generic" = any shape), or NULL for invalid arguments.  Host only; for tests and reports. */
+ * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the family
+ * reported for V0 = V_out = NULL.  Host only; for tests and reports. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
 
 #ifdef __cplusplus

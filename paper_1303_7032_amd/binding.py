@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_prepare.argtypes = [vp, ci, ci, vp, sz, vp]
         L.gbnn_retrieve.restype = ci
         L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
+        L.gbnn_retrieve_symbols.restype = ci
+        L.gbnn_retrieve_symbols.argtypes = [vp, ci, ci, vp, i64, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         L.gbnn_strerror.restype = ctypes.c_char_p
         L.gbnn_strerror.argtypes = [ci]
         L.gbnn_retrieve_path.restype = ctypes.c_char_p
@@ -160,6 +162,45 @@ def gbnn_retrieve(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma
                                gamma, max_iters, iters_out.data_ptr() if iters_out is not None else 0,
                                workspace.data_ptr(), workspace.numel(), _stream(V0)))
     return V_out, iters_out
+
+
+SYM_NONE, SYM_AMBIGUOUS = -1, -2
+
+
+def gbnn_retrieve_symbols(W: torch.Tensor, C: int, L: int, probes: torch.Tensor, rule, gamma: int = 1,
+                          max_iters: int = 20, bits_out: torch.Tensor | None = None,
+                          symbols_out: torch.Tensor | None = None, iters_out: torch.Tensor | None = None,
+                          workspace: torch.Tensor | None = None, want_bits: bool = True, want_symbols: bool = True,
+                          want_iters: bool = True):
+    """Retrieve the K partially erased messages of probes (int32[K][C], -1 = erased).
+    Returns (bits_out int32[K][nw] or None, symbols_out int32[K][C] or None, iters_out or None);
+    outputs not supplied are allocated with torch unless switched off by the want_* flags."""
+    r = _rule(rule)
+    _dev(W, torch.int32, "W")
+    _dev(probes, torch.int32, "probes")
+    if W.numel() * 4 != gbnn_w_bytes(C, L) or probes.numel() % C:
+        _check(ERRORS["SHAPE"])
+    K = probes.numel() // C
+    nw = gbnn_w_row_words(C, L)
+    if bits_out is None and want_bits:
+        bits_out = torch.empty((K, nw), dtype=torch.int32, device=probes.device)
+    if symbols_out is None and want_symbols:
+        symbols_out = torch.empty((K, C), dtype=torch.int32, device=probes.device)
+    if iters_out is None and want_iters:
+        iters_out = torch.empty(K, dtype=torch.int32, device=probes.device)
+    for t, cnt, name in ((bits_out, K * nw, "bits_out"), (symbols_out, K * C, "symbols_out"), (iters_out, K, "iters_out")):
+        if t is not None:
+            _dev(t, torch.int32, name)
+            if t.numel() != cnt:
+                _check(ERRORS["SHAPE"])
+    if workspace is None:
+        workspace = gbnn_prepare(W, C, L)
+    _dev(workspace, torch.uint8, "workspace")
+    ptr = lambda t: t.data_ptr() if (t is not None and K) else 0
+    _check(lib().gbnn_retrieve_symbols(W.data_ptr(), C, L, ptr(probes), K, r, gamma, max_iters, ptr(bits_out),
+                                       ptr(symbols_out), ptr(iters_out), workspace.data_ptr(), workspace.numel(),
+                                       _stream(probes)))
+    return bits_out, symbols_out, iters_out
 
 
 def gbnn_retrieve_path(C: int, L: int, rule, V0: torch.Tensor | None = None, V_out: torch.Tensor | None = None) -> str:

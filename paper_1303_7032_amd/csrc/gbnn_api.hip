@@ -26,7 +26,7 @@ int pick_path(int C, int L, const void *V0, const void *Vout)
 {
     const char *force = std::getenv("GBNN_FORCE_GENERIC");
     if (force && force[0] == '1') return 0;
-    if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;
+    if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;  // (the message boundary passes nullptr: no constraint)
     const char *wave = std::getenv("GBNN_FORCE_WAVE");
     if (!(wave && wave[0] == '1')) {
         if (half_wave_serves(C, L)) return kHalfPath;
@@ -79,6 +79,33 @@ int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t worksp
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
+// Checks common to both boundaries, then the launch.
+static int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K, int rule, int gamma,
+                           int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < gbnn_workspace_bytes(C, L, K, rule))
+        return GBNN_ERR_WORKSPACE;
+    if (K == 0) return GBNN_OK;
+    a.W = W;
+    a.nw = (int)gbnn_w_row_words(C, L);
+    a.Wb = static_cast<const uint32_t *>(workspace);
+    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
+    a.iters = iters_out;
+    a.K = K;
+    a.C = C;
+    a.L = L;
+    a.n = C * L;
+    a.rule = rule;
+    a.gamma = gamma;
+    a.max_iters = max_iters;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int path = pick_path(C, L, a.V0, a.Vout);
+    const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
+                         : path            ? launch_retrieve_wave(a, path, s)
+                                           : launch_retrieve_generic(a, s);
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
 int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
                   void *stream)
@@ -88,32 +115,26 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
     if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
     if (max_iters < 1) return GBNN_ERR_ITERS;
     if (!W || (K > 0 && (!V0 || !V_out))) return GBNN_ERR_NULL;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < gbnn_workspace_bytes(C, L, K, rule))
-        return GBNN_ERR_WORKSPACE;
-    if (K == 0) return GBNN_OK;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    RetrieveArgs a;
-    a.W = W;
-    a.nw = (int)gbnn_w_row_words(C, L);
-    a.Wb = static_cast<const uint32_t *>(workspace);
-    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
+    RetrieveArgs a{};
     a.V0 = V0;
     a.Vout = V_out;
-    a.iters = iters_out;
-    a.K = K;
-    a.C = C;
-    a.L = L;
-    a.n = C * L;
-    a.rule = rule;
-    a.gamma = gamma;
-    a.max_iters = max_iters;
+    return retrieve_common(a, W, C, L, K, rule, gamma, max_iters, iters_out, workspace, workspace_bytes, stream);
+}
 
-    const int path = pick_path(C, L, V0, V_out);
-    const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
-                         : path            ? launch_retrieve_wave(a, path, s)
-                                           : launch_retrieve_generic(a, s);
-    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes, int64_t K, int rule, int gamma,
+                          int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!shape_ok(C, L) || K < 0) return GBNN_ERR_SHAPE;
+    if (!rule_ok(rule)) return GBNN_ERR_RULE;
+    if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
+    if (max_iters < 1) return GBNN_ERR_ITERS;
+    if (!W || (K > 0 && !probes)) return GBNN_ERR_NULL;
+    RetrieveArgs a{};
+    a.sym_in = probes;
+    a.bits_out = bits_out;
+    a.sym_out = symbols_out;
+    return retrieve_common(a, W, C, L, K, rule, gamma, max_iters, iters_out, workspace, workspace_bytes, stream);
 }
 
 const char *gbnn_strerror(int code)

@@ -61,6 +61,43 @@ __device__ __forceinline__ uint32_t group_or(uint32_t v)
     return v;
 }
 
+// Sum over the 2^LG lanes of this lane's group, left in every lane of the group (same butterfly).
+template <int CTRL>
+__device__ __forceinline__ uint32_t add_dpp(uint32_t v)
+{
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int LG>
+__device__ __forceinline__ uint32_t group_add(uint32_t v)
+{
+    if (LG >= 1) v = add_dpp<0xB1>(v);
+    if (LG >= 2) v = add_dpp<0x4E>(v);
+    if (LG >= 3) v = add_dpp<0x141>(v);
+    if (LG >= 4) v = add_dpp<0x140>(v);
+    if (LG >= 5) v += (uint32_t)__shfl_xor((int)v, 16);
+    if (LG >= 6) v += (uint32_t)__shfl_xor((int)v, 32);
+    return v;
+}
+
+// The message boundary, per cluster.  word_in_cluster = index of this lane's word inside its cluster.
+// Probe side: the word of a cluster whose symbol is s (anything outside [0, L) = erased, Section II-A).
+__device__ __forceinline__ uint32_t symbol_word(int32_t s, uint32_t L, uint32_t word_in_cluster)
+{
+    const bool here = (uint32_t)s < L && ((uint32_t)s >> 5) == word_in_cluster;
+    return here ? 1u << ((uint32_t)s & 31u) : 0u;
+}
+// Result side: the symbol of this lane's cluster given its word v of the final activity: the index of
+// the active neuron if the cluster holds exactly one, -1 if none, -2 if several (Section V-B).
+template <int LG>
+__device__ __forceinline__ int32_t cluster_symbol(uint32_t v, uint32_t word_in_cluster)
+{
+    const uint32_t pc = __popc(v);
+    const uint32_t tot = group_add<LG>(pc);
+    const uint32_t pos = (word_in_cluster << 5) + (uint32_t)__builtin_ctz(v | 0x80000000u);
+    const uint32_t possum = group_add<LG>(pc == 1u ? pos : 0u);
+    return tot == 1u ? (int32_t)possum : (tot == 0u ? -1 : -2);
+}
+
 // Bit-sliced counting.  pl[q] holds binary digit q of a per-neuron counter, 32 neurons per word.
 // full adder / half adder on bit vectors
 // (outputs may alias inputs)

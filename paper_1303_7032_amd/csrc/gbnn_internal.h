@@ -15,8 +15,11 @@ struct RetrieveArgs {
     const uint32_t *W;    // canonical adjacency, uint32[n][nw]
     const uint32_t *Wb;   // W with all-one intra-cluster blocks, uint32[n][nw], followed directly by
     const uint32_t *has;  // the cluster summaries, uint32[C][nw]: bit i of row c' = "i is in c' or adjacent to a neuron of c'"
-    const uint8_t *V0;    // uint8[K][n]
-    uint8_t *Vout;        // uint8[K][n]
+    const uint8_t *V0;    // uint8[K][n]                       } the activity boundary (gbnn_retrieve);
+    uint8_t *Vout;        // uint8[K][n]                       } both nullptr at the message boundary
+    const int32_t *sym_in;  // int32[K][C] or nullptr: the message boundary (gbnn_retrieve_symbols) when set
+    uint32_t *bits_out;     // uint32[K][nw] or nullptr        } outputs of the message boundary
+    int32_t *sym_out;       // int32[K][C] or nullptr          }
     int32_t *iters;       // int32[K] or nullptr
     int64_t K;
     int C, L, n, nw;

@@ -150,14 +150,27 @@ __global__ __launch_bounds__(64) void k_retrieve_generic(RetrieveArgs a)
     const int lane = g.lane;
 
     for (int64_t k = blockIdx.x; k < a.K; k += gridDim.x) {
-        const uint8_t *src = a.V0 + k * a.n;
-        for (int w = lane; w < a.nw; w += 64) {
-            uint32_t word = 0u;
-            for (int b = 0; b < 32; ++b) {
-                const int i = 32 * w + b;
-                if (i < a.n) word |= (uint32_t)(src[i] & 1u) << b;
+        if (a.sym_in) {
+            // the message boundary: one symbol per cluster, anything outside [0, L) = erased (Section II-A)
+            for (int w = lane; w < a.nw; w += 64) g.v[w] = 0u;
+            __syncthreads();
+            for (int c = lane; c < a.C; c += 64) {
+                const int32_t sy = a.sym_in[k * a.C + c];
+                if (sy >= 0 && sy < a.L) {
+                    const int i = c * a.L + sy;
+                    atomicOr(&g.v[i >> 5], 1u << (i & 31));  // clusters may share a word
+                }
             }
-            g.v[w] = word;
+        } else {
+            const uint8_t *src = a.V0 + k * a.n;
+            for (int w = lane; w < a.nw; w += 64) {
+                uint32_t word = 0u;
+                for (int b = 0; b < 32; ++b) {
+                    const int i = 32 * w + b;
+                    if (i < a.n) word |= (uint32_t)(src[i] & 1u) << b;
+                }
+                g.v[w] = word;
+            }
         }
         __syncthreads();
 
@@ -221,12 +234,29 @@ __global__ __launch_bounds__(64) void k_retrieve_generic(RetrieveArgs a)
         }
 
         if (a.iters && lane == 0) a.iters[k] = it;
-        uint8_t *dst = a.Vout + k * a.n;
-        for (int w = lane; w < a.nw; w += 64) {
-            const uint32_t word = g.v[w];
-            for (int b = 0; b < 32; ++b) {
-                const int i = 32 * w + b;
-                if (i < a.n) dst[i] = (uint8_t)((word >> b) & 1u);
+        if (a.sym_in) {
+            if (a.bits_out)
+                for (int w = lane; w < a.nw; w += 64) a.bits_out[k * a.nw + w] = g.v[w];
+            if (a.sym_out) {
+                // the symbol of a cluster: its active neuron if it has exactly one, -1 none, -2 several
+                for (int c = lane; c < a.C; c += 64) {
+                    int cnt = 0, pos = 0;
+                    for (int w = g.first_word(c); w <= g.last_word(c); ++w) {
+                        const uint32_t m = g.v[w] & own_mask(c, a.L, w);
+                        if (m) pos = 32 * w + __builtin_ctz(m) - c * a.L;
+                        cnt += __popc(m);
+                    }
+                    a.sym_out[k * a.C + c] = cnt == 1 ? pos : (cnt == 0 ? -1 : -2);
+                }
+            }
+        } else {
+            uint8_t *dst = a.Vout + k * a.n;
+            for (int w = lane; w < a.nw; w += 64) {
+                const uint32_t word = g.v[w];
+                for (int b = 0; b < 32; ++b) {
+                    const int i = 32 * w + b;
+                    if (i < a.n) dst[i] = (uint8_t)((word >> b) & 1u);
+                }
             }
         }
         __syncthreads();

@@ -413,15 +413,22 @@ k_retrieve_wave(RetrieveArgs a)
     const int64_t nwaves = (int64_t)gridDim.x * wpb;
 
     for (int64_t k = wave; k < a.K; k += nwaves) {
-        // ---- probe load: 32 bytes per word, packed to bits
+        // ---- probe load: 32 bytes per word, packed to bits; or one symbol per cluster
         uint32_t v[NW];
-        const uint8_t *src = a.V0 + k * a.n;
+        if (a.sym_in) {
+            const int32_t *sym = a.sym_in + k * a.C;
 #pragma unroll
-        for (int t = 0; t < NW; ++t) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
-            const uint4 lo = p[0];
-            const uint4 hi = p[1];
-            v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
+            for (int t = 0; t < NW; ++t)
+                v[t] = x.valid[t] ? symbol_word(sym[x.myc[t]], (uint32_t)a.L, (uint32_t)x.lane & (LW - 1)) : 0u;
+        } else {
+            const uint8_t *src = a.V0 + k * a.n;
+#pragma unroll
+            for (int t = 0; t < NW; ++t) {
+                const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
+                const uint4 lo = p[0];
+                const uint4 hi = p[1];
+                v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
+            }
         }
 
         int it = 0;
@@ -565,13 +572,28 @@ k_retrieve_wave(RetrieveArgs a)
 
         // ---- result store
         if (a.iters && x.lane == 0) a.iters[k] = it;
-        uint8_t *dstb = a.Vout + k * a.n;
+        if (a.sym_in) {
+            if (a.bits_out) {
 #pragma unroll
-        for (int t = 0; t < NW; ++t) {
-            if (x.valid[t]) {
-                uint4 *dst = reinterpret_cast<uint4 *>(dstb + x.woffb[t] * 8u);
-                dst[0] = spread16(v[t] & 0xFFFFu);
-                dst[1] = spread16(v[t] >> 16);
+                for (int t = 0; t < NW; ++t)
+                    if (x.valid[t]) a.bits_out[k * a.nw + t * 64 + x.lane] = v[t];
+            }
+            if (a.sym_out) {
+#pragma unroll
+                for (int t = 0; t < NW; ++t) {
+                    const int32_t sy = cluster_symbol<LG>(v[t], (uint32_t)x.lane & (LW - 1));
+                    if (x.islead[t]) a.sym_out[k * a.C + x.myc[t]] = sy;
+                }
+            }
+        } else {
+            uint8_t *dstb = a.Vout + k * a.n;
+#pragma unroll
+            for (int t = 0; t < NW; ++t) {
+                if (x.valid[t]) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(dstb + x.woffb[t] * 8u);
+                    dst[0] = spread16(v[t] & 0xFFFFu);
+                    dst[1] = spread16(v[t] >> 16);
+                }
             }
         }
     }

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"gbnn_store", "gbnn_prepare", "gbnn_retrieve", "gbnn_w_bytes", "gbnn_workspace_bytes", "gbnn_strerror"} <= set(names)
+    assert {"gbnn_store", "gbnn_prepare", "gbnn_retrieve", "gbnn_retrieve_symbols", "gbnn_w_bytes", "gbnn_workspace_bytes", "gbnn_strerror"} <= set(names)
     for name in names:
         assert getattr(lib, name) is not None, name
 
@@ -61,6 +61,23 @@ def test_retrieve_argument_errors(lib):
     assert call(cap=0) == E["ITERS"]
     assert call(W=0) == E["NULL"] and call(V0=0) == E["NULL"] and call(Vout=0) == E["NULL"]
     assert call(wsp=0) == E["WORKSPACE"] and call(wsp=fake * 16 + 8) == E["WORKSPACE"] and call(wsb=16) == E["WORKSPACE"]
+
+
+def test_retrieve_symbols_argument_errors(lib):
+    E = gb.ERRORS
+    fake = 0x1000
+    ws = 1 << 24
+
+    def call(W=fake, C=8, L=256, P=fake, K=4, rule=1, gamma=1, cap=20, bits=fake, sym=fake, it=0, wsp=fake * 16, wsb=ws):
+        return lib.gbnn_retrieve_symbols(W, C, L, P, K, rule, gamma, cap, bits, sym, it, wsp, wsb, 0)
+
+    assert call(C=1) == E["SHAPE"] and call(L=0) == E["SHAPE"] and call(K=-1) == E["SHAPE"]
+    assert call(rule=3) == E["RULE"]
+    assert call(gamma=-1) == E["GAMMA"] and call(gamma=32768) == E["GAMMA"]
+    assert call(cap=0) == E["ITERS"]
+    assert call(W=0) == E["NULL"] and call(P=0) == E["NULL"]
+    assert call(wsp=0) == E["WORKSPACE"] and call(wsb=16) == E["WORKSPACE"]
+    assert call(K=0, P=0, bits=0, sym=0) == gb.GBNN_OK     # nothing to do, nothing launched
 
 
 def test_store_argument_errors(lib):

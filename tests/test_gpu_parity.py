@@ -176,6 +176,70 @@ def test_probes_from_stored_messages(networks, C, L, M, e, K, rule):
             break  # gamma is ignored by the other rules
 
 
+def dev_retrieve_symbols(W, C, L, probes, rule, gamma, cap, force_generic=False, force_wave=False, **kw):
+    want = {"GBNN_FORCE_GENERIC": "1" if force_generic else "0", "GBNN_FORCE_WAVE": "1" if force_wave else "0"}
+    old = {k: os.environ.get(k) for k in want}
+    os.environ.update(want)
+    try:
+        bits, sym, it = gb.gbnn_retrieve_symbols(W, C, L, torch.from_numpy(probes).cuda(), rule, gamma, cap, **kw)
+        torch.cuda.synchronize()
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    return [None if t is None else t.cpu().numpy() for t in (bits, sym, it)]
+
+
+@pytest.mark.parametrize("C,L,M,e,K", SHAPES)
+@pytest.mark.parametrize("rule", RULES)
+def test_messages_at_the_boundary(networks, C, L, M, e, K, rule):
+    """gbnn_retrieve_symbols (symbols in; packed bits, symbols and pass counts out) against the
+    oracle's encode -> retrieve -> decode, on every kernel family that serves the shape.  Besides
+    erased clusters the probes hold wrong symbols (so that clusters end empty or ambiguous) and
+    out-of-range entries (= erased)."""
+    msgs, Wo, Wd = networks(C, L, M)
+    q, er = inputs.make_probe_plan(C, M, K, e, 11 + C + L)
+    probes = msgs[q].copy()
+    probes[er] = -1
+    rng = np.random.default_rng(C * 77 + L)
+    for k in range(0, K, 5):                       # a wrong symbol in one known cluster
+        c = int(rng.integers(C))
+        probes[k, c] = int(rng.integers(L))
+    probes[1::7, 0] = L + 3                        # outside [0, L): erased
+    probes[2::9, C - 1] = -12345
+    cap = 20 if rule != "sum_of_sum" else 4
+    rbits, rsym, rit = orc.retrieve_symbols(Wo, C, L, probes, rule, 1, cap)
+    for nm, kw in [("default", {})] + other_paths(C, L, rule):
+        if nm == "generic" and K > 300:
+            continue
+        bits, sym, it = dev_retrieve_symbols(Wd, C, L, probes, rule, 1, cap, **kw)
+        assert (bits.view(np.uint32) == rbits).all(), f"{rule} {nm}: packed bits differ"
+        bad = np.nonzero((sym != rsym).any(axis=1))[0]
+        assert bad.size == 0, f"{rule} {nm}: symbols differ at probes {bad[:5]}: {sym[bad[:2]]} vs {rsym[bad[:2]]}"
+        assert (it == rit).all(), f"{rule} {nm}: iters differ"
+    # each output alone, and none at all
+    bits, sym, it = dev_retrieve_symbols(Wd, C, L, probes, rule, 1, cap, want_symbols=False, want_iters=False)
+    assert sym is None and it is None and (bits.view(np.uint32) == rbits).all()
+    bits, sym, it = dev_retrieve_symbols(Wd, C, L, probes, rule, 1, cap, want_bits=False)
+    assert bits is None and (sym == rsym).all() and (it == rit).all()
+
+
+def test_messages_at_the_boundary_edge_cases(networks):
+    C, L, M = 8, 128, 5000
+    msgs, Wo, Wd = networks(C, L, M)
+    bits, sym, it = gb.gbnn_retrieve_symbols(Wd, C, L, torch.zeros((0, C), dtype=torch.int32, device="cuda"), "hybrid")
+    assert bits.numel() == 0 and sym.numel() == 0 and it.numel() == 0
+    for K in (1, 2, 3):                                   # fewer probes than a wave carries; odd K
+        probes = msgs[:K].copy()
+        probes[:, 1] = -1
+        for rule in RULES:
+            rbits, rsym, rit = orc.retrieve_symbols(Wo, C, L, probes, rule, 1, 6)
+            bits, sym, it = dev_retrieve_symbols(Wd, C, L, probes, rule, 1, 6)
+            assert (bits.view(np.uint32) == rbits).all() and (sym == rsym).all() and (it == rit).all()
+
+
 @pytest.mark.parametrize("C,L,M", [(4, 16, 50), (5, 12, 200), (8, 32, 300), (8, 128, 5000), (8, 256, 20000),
                                     (16, 512, 100000), (32, 32, 700), (2, 512, 30000)])
 @pytest.mark.parametrize("rule", RULES)
