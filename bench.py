@@ -111,7 +111,8 @@ def main() -> int:
     abytes = algorithmic_bytes_per_probe(n, K, True) * K
     for r in rules:
         ms = np.array([a.elapsed_time(b) for a, b in ev[r]])
-        per_rule[r] = {"ms_avg": float(ms.mean()), "ms_min": float(ms.min()), "qps": K / (ms.mean() * 1e-3),
+        per_rule[r] = {"ms_avg": float(ms.mean()), "ms_median": float(np.median(ms)), "ms_min": float(ms.min()),
+                       "qps": K / (ms.mean() * 1e-3),
                        "hbm_GBs": abytes / (ms.mean() * 1e-3) / 1e9}
     dominant = max(rules, key=lambda r: per_rule[r]["ms_avg"])
     achieved = per_rule[dominant]["hbm_GBs"]
@@ -119,6 +120,47 @@ def main() -> int:
     tfile = ROOT / "profiles" / "hbm_traffic.json"
     if tfile.exists():
         traffic = json.loads(tfile.read_text()).get(f"{args.workload}:{dominant}")
+
+    # ---- reference points after the timed region: a plain device copy of the probe tensor (what the memory
+    # system gives a kernel that only reads K*n bytes and writes K*n bytes), and the same retrieval with
+    # messages at the boundary (gbnn_retrieve_symbols: symbols in, packed bits + symbols + pass counts out)
+    cp = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    scratch = torch.empty_like(V0d)
+    for i in range(3 + len(cp)):
+        if i >= 3:
+            cp[i - 3][0].record()
+        scratch.view(torch.int64).copy_(V0d.view(torch.int64))
+        if i >= 3:
+            cp[i - 3][1].record()
+    torch.cuda.synchronize()
+    copy_ms = float(np.median([a.elapsed_time(b) for a, b in cp]))
+    copy_GBs = 2.0 * K * n / (copy_ms * 1e-3) / 1e9
+    del scratch
+
+    probes_h = msgs[q].copy()
+    probes_h[er] = -1
+    probes_d = torch.from_numpy(probes_h).cuda()
+    nw = gb.gbnn_w_row_words(C, L)
+    mb_bits = torch.empty((K, nw), dtype=torch.int32, device="cuda")
+    mb_sym = torch.empty((K, C), dtype=torch.int32, device="cuda")
+    mb_it = torch.empty(K, dtype=torch.int32, device="cuda")
+    mb_bytes = (4.0 * C + 4.0 * nw + 4.0 * C + 4.0) * K + n * n / 8.0
+    message_boundary = {}
+    for r in rules:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for i in range(3 + args.steps):
+            if i >= 3:
+                evs[i - 3][0].record()
+            gb.gbnn_retrieve_symbols(W, C, L, probes_d, r, w.gamma, w.max_iters, bits_out=mb_bits, symbols_out=mb_sym,
+                                     iters_out=mb_it, workspace=ws)
+            if i >= 3:
+                evs[i - 3][1].record()
+        torch.cuda.synchronize()
+        ms = np.array([a.elapsed_time(b) for a, b in evs])
+        same = bool((mb_it == iters[r]).all())
+        message_boundary[r] = {"ms_avg": float(ms.mean()), "ms_median": float(np.median(ms)), "qps": K / (ms.mean() * 1e-3),
+                               "hbm_bytes_per_launch": mb_bytes, "hbm_GBs": mb_bytes / (ms.mean() * 1e-3) / 1e9,
+                               "same_pass_counts_as_activity_boundary": same}
 
     if args.calibrate_copy:
         for _ in range(3):
@@ -156,8 +198,14 @@ def main() -> int:
             ref, itref, _ = refs[r]
             per_rule[r]["matches_oracle_on_sample"] = bool(
                 (outs[r][:Ks].cpu().numpy() == ref).all() and (iters[r][:Ks].cpu().numpy() == itref).all())
+        K1 = min(K, 4096)
+        t0 = time.perf_counter()
+        for r in rules:
+            orc.retrieve(Wo, C, L, V0[:K1], r, w.gamma, w.max_iters, nthreads=1)
+        one_s = time.perf_counter() - t0
         cpu = {"value": Ks * len(rules) / cpu_s, "unit": "queries/s", "cores": used, "kind": "oracle",
-               "sample": f"first {Ks} probes of the batch, rules {'+'.join(rules)}, {cpu_s:.2f} s wall on {used} threads"}
+               "sample": f"first {Ks} probes of the batch, rules {'+'.join(rules)}, {cpu_s:.2f} s wall on {used} threads",
+               "single_thread_value": K1 * len(rules) / one_s, "single_thread_sample": f"first {K1} probes, {one_s:.2f} s"}
 
     line = {
         "metric": "retrieved queries/sec at c=8,l=256 (sum-of-max, hybrid)" if (C, L) == (8, 256)
@@ -172,9 +220,11 @@ def main() -> int:
                    "kernel_path": gb.gbnn_retrieve_path(C, L, rules[0], V0d, outs[rules[0]])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": f"gbnn_retrieve[{dominant}]",
-                     "algorithmic_bytes_per_launch": abytes},
+                     "algorithmic_bytes_per_launch": abytes,
+                     "device_copy_GBs_same_run": copy_GBs, "frac_of_device_copy": achieved / copy_GBs},
         "cpu_baseline": cpu,
         "per_rule": per_rule,
+        "message_boundary": message_boundary,
         "store": {"messages": w.M, "seconds_incl_launch_and_sync": store_s,
                   "prepare_seconds_incl_launch_and_sync": prepare_s},
     }

@@ -355,5 +355,19 @@ def test_full_configuration(name):
         assert orc.error_rate(out, target) == orc.error_rate(ref, target)
         finals[rule] = out
         del ref
+        # the message boundary at full size: same final vectors, as packed bits and as symbols
+        probes = msgs[q].copy()
+        probes[er] = -1
+        bits, sym, it2 = dev_retrieve_symbols(Wd, w.C, w.L, probes, rule, w.gamma, w.max_iters)
+        assert (it2 == it).all()
+        nw = (w.n + 31) // 32
+        padded = np.zeros((w.K, nw * 32), dtype=np.uint8)
+        padded[:, :w.n] = out
+        assert (bits.view(np.uint32) == np.packbits(padded, axis=1, bitorder="little").view("<u4")).all()
+        act = out.reshape(w.K, w.C, w.L)
+        cnt = act.sum(axis=2)
+        want = np.where(cnt == 1, act.argmax(axis=2), np.where(cnt == 0, -1, -2)).astype(np.int32)
+        assert (sym == want).all()
+        del padded, act
     if "hybrid" in finals and "sum_of_max" in finals:
         assert (finals["hybrid"] == finals["sum_of_max"]).all()      # Theorem 4
