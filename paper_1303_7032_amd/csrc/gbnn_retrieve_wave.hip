@@ -82,10 +82,11 @@ __device__ __forceinline__ bool some_group_empty(const Ctx<NW> &x, int t, uint64
 // bits of pw[] (row = neuron index, ascending) followed by one summary row (row n + c) for every
 // lane flagged in summask[] (the first lane of a fully active cluster c).  At most kListMax
 // entries are taken, whole words at a time and in order; what is taken is cleared from pw[] and
-// summask[], so that calling again continues where this chunk stopped.  Returns the entry count.
+// summask[], so that calling again continues where this chunk stopped.  Returns the entry count; or -1,
+// as soon as the set bits of pw[] are seen to number more than give_up (pw[], list are then unusable).
 template <int NW>
 __device__ __forceinline__ int take_chunk(const Ctx<NW> &x, uint32_t (&pw)[NW], uint64_t (&summask)[NW],
-                                          uint32_t &list)
+                                          uint32_t &list, int give_up = 1 << 30)
 {
     int base = 0;
     bool open = true;  // false once something had to be left for the next chunk
@@ -104,6 +105,7 @@ __device__ __forceinline__ int take_chunk(const Ctx<NW> &x, uint32_t (&pw)[NW], 
                 tot += __builtin_popcountll(mk);
                 mk = ballot(pc > k);
             }
+            if (base + tot > give_up) return -1;
             uint32_t w = pw[t];
             if (base + tot > kListMax) {
                 // keep the words that fit entirely; the rest of this slot and all later slots wait
@@ -382,6 +384,96 @@ __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (
     }
 }
 
+// The passes after the first on the adjacency matrix of the candidates (sum-of-max and hybrid).
+//
+// Setting: every known cluster of the probe holds one active neuron, all of them survived pass 1 (so
+// they are pairwise adjacent), and pass 1 left T <= 32 active neurons ("candidates") in the erased
+// clusters, at least one in each.  Every candidate is adjacent to every known neuron (pass 1 took
+// the AND of their rows), and neurons that are off stay off (Lemma 1), so from here on only the
+// adjacency among the candidates decides: candidate q stays on iff every other erased cluster holds
+// a candidate that is still on and adjacent to q; the known neurons stay on as long as every erased
+// cluster keeps a candidate (and all go off in the pass after one has lost its last: no cluster
+// signals them any more).  Lane q < T holds candidate q (ascending neuron index, so a cluster is a
+// run of lanes) and A = its adjacency over the candidates, bit q' = w between candidates q' and q;
+// bits of its own cluster are ones (the table's intra-cluster blocks are all ones).  A pass is then
+// "does A & alive have a bit in every cluster's run of positions", a zero-field test with the runs as
+// fields; no further rows are fetched and no lists built.  Each candidate's row is fetched once, to
+// fill A: lane q takes bit j_q of row j_q' from the lane that holds that word (ds_bpermute).
+// On entry p = 1 passes are done; on exit v holds the final vector and the return value is the
+// iteration count to report.  `list` / T come from take_chunk over the candidates.
+template <int NW, int RULE, int LG>
+__device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t (&probe)[NW], uint32_t list, int T,
+                                                int max_iters, uint32_t (&v)[NW])
+{
+    const bool inl = x.lane < T;
+    const uint32_t jlast = readlane(list, T - 1) - 1u;
+    const uint32_t jq = inl ? list - 1u : jlast;  // lanes past the end repeat the last candidate
+    const uint32_t cq = jq >> (LG + 5);
+    const uint32_t below = (uint32_t)__builtin_amdgcn_update_dpp((int)0xFFFFFFFFu, (int)cq, 0x138 /* wave_shr:1 */, 0xf,
+                                                                 0xf, false);
+    const uint32_t maskT = T == 32 ? 0xFFFFFFFFu : (1u << T) - 1u;
+    const uint32_t S = (uint32_t)ballot(inl && cq != below);          // first position of every cluster's run
+    const uint32_t E = ((S >> 1) | (1u << (T - 1))) & maskT;          // last position of every run
+    const uint32_t wq = jq >> 5;                                      // word of the candidate: slot wq / 64, lane wq % 64
+    const uint32_t waddr = (wq & 63u) << 2;
+    const uint32_t bitpos = jq & 31u;
+    const uint32_t offv = __umul24(jq, x.rowbytes);
+
+    uint32_t A = 0u;
+    for (int i0 = 0; i0 < T; i0 += 4) {
+        uint32_t r[4][NW];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+        uint32_t t = 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((int)waddr, (int)r[q][0]);
+#pragma unroll
+            for (int u = 1; u < NW; ++u) {
+                const uint32_t wu = (uint32_t)__builtin_amdgcn_ds_bpermute((int)waddr, (int)r[q][u]);
+                w = (wq >> 6) == (uint32_t)u ? wu : w;
+            }
+            t |= ((w >> bitpos) & 1u) << q;
+        }
+        A |= t << i0;
+    }
+
+    uint32_t m = maskT;          // candidates still on
+    bool known_on = true;        // the known neurons (sum-of-max switches them off with an emptied cluster)
+    bool changed = true;         // pass 1 counts as a change for the hybrid; for sum-of-max the caller checked
+    int p = 1, it;
+    for (;;) {
+        if (!changed) { it = p; break; }
+        if (p == max_iters) { it = -p; break; }
+        ++p;
+        if (((m - S) & ~m & E) != 0u) {
+            // some erased cluster has no candidate left: nobody receives a signal from it
+            changed = m != 0u || (RULE == GBNN_SUM_OF_MAX && known_on);
+            m = 0u;
+            if (RULE == GBNN_SUM_OF_MAX) known_on = false;
+        } else {
+            const uint32_t y = A & m;
+            const uint32_t off = (uint32_t)ballot(((y - S) & ~y & E) != 0u);
+            changed = (m & off) != 0u;
+            m &= ~off;
+        }
+    }
+
+    // final vector: the probe's known neurons (unless switched off) and the candidates still on
+#pragma unroll
+    for (int u = 0; u < NW; ++u) v[u] = known_on ? probe[u] : 0u;
+    while (m) {
+        const int q = __builtin_ctz(m);
+        m &= m - 1u;
+        const uint32_t j = readlane(jq, q);
+        const uint32_t w = j >> 5;
+#pragma unroll
+        for (int u = 0; u < NW; ++u)
+            if ((w >> 6) == (uint32_t)u && (uint32_t)x.lane == (w & 63u)) v[u] |= 1u << (j & 31u);
+    }
+    return it;
+}
+
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
 // Register budget: 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per lane (2 for sum-of-sum at 4).
 template <int NW, int RULE, int LG>
@@ -437,7 +529,9 @@ k_retrieve_wave(RetrieveArgs a)
             bool erased[NW];
 #pragma unroll
             for (int t = 0; t < NW; ++t) erased[t] = x.valid[t] && group_or<LG>(v[t]) == 0u;
-            uint32_t acc[NW], d[NW];
+            uint32_t acc[NW], d[NW], probe[NW];
+#pragma unroll
+            for (int t = 0; t < NW; ++t) probe[t] = v[t];
             int p = 1;
             bool changed = true;
             if (RULE == GBNN_SUM_OF_MAX) {
@@ -495,7 +589,41 @@ k_retrieve_wave(RetrieveArgs a)
                 }
                 // the stop test is made only after a bail-out-early pass (Algorithm 2, line 13)
             }
-            for (;;) {
+            // The usual probe (one active neuron per known cluster, all of them still on, a few candidates
+            // in every erased cluster) finishes on the candidates' adjacency matrix; any other probe, and
+            // a probe whose pass 1 changed nothing, takes the general loop below.
+            bool finished = false;
+            if (NW == 1 && changed) {  // (with more words per lane filling the matrix costs what it saves)
+                uint64_t multi = 0, lost = 0, bare = 0;
+                int nz = 0, known = 0;
+                uint32_t pw[NW];
+                uint64_t summask[NW];
+#pragma unroll
+                for (int t = 0; t < NW; ++t) {
+                    nz += __builtin_popcountll(ballot(probe[t] != 0u));
+                    multi |= ballot((probe[t] & (probe[t] - 1u)) != 0u);
+                    lost |= ballot(!erased[t] && acc[t] != probe[t]);
+                    pw[t] = erased[t] ? acc[t] : 0u;
+                    bare |= ballot(erased[t] && group_or<LG>(pw[t]) == 0u);
+                    summask[t] = 0;
+                    known += __builtin_popcountll(ballot(x.islead[t] && !erased[t]));
+                }
+                // a cheap lower bound of the number of candidates: lanes with one, plus lanes with two or more
+                int atleast = 0;
+#pragma unroll
+                for (int t = 0; t < NW; ++t)
+                    atleast += __builtin_popcountll(ballot(pw[t] != 0u)) +
+                               __builtin_popcountll(ballot((pw[t] & (pw[t] - 1u)) != 0u));
+                if (!multi && !lost && !bare && nz == known && atleast <= 32) {
+                    uint32_t list;
+                    const int T = take_chunk(x, pw, summask, list, 32);
+                    if (T >= 1) {
+                        it = candidate_passes<NW, RULE, LG>(x, probe, list, T, a.max_iters, v);
+                        finished = true;
+                    }
+                }
+            }
+            while (!finished) {
 #pragma unroll
                 for (int t = 0; t < NW; ++t) v[t] = acc[t];
                 if (!changed) { it = p; break; }

@@ -281,6 +281,37 @@ def test_arbitrary_binary_probes(networks, C, L, M, rule):
             break
 
 
+@pytest.mark.parametrize("M", [20000, 30000])
+@pytest.mark.parametrize("rule", ["sum_of_max", "hybrid"])
+def test_later_passes_many_caps_and_dying_clusters(networks, M, rule):
+    """Passes after the first, at every cap, on probes that converge early, late, hit the cap, or lose
+    a whole cluster (after which everything switches off): stored messages with 3-6 erased clusters,
+    half of them with one wrong known symbol."""
+    C, L, K = 8, 256, 600
+    msgs, Wo, Wd = networks(C, L, M)
+    rng = np.random.default_rng(M)
+    parts = []
+    for e in (3, 4, 5, 6):
+        q, er = inputs.make_probe_plan(C, M, K // 4, e, 40 + e)
+        sym = msgs[q].copy()
+        for k in range(0, len(sym), 2):
+            known = np.nonzero(~er[k])[0]
+            sym[k, known[int(rng.integers(len(known)))]] = int(rng.integers(L))
+        parts.append(inputs.one_hot(sym, L, er))
+    V0 = np.concatenate(parts)
+    seen_dead_late = seen_capped = 0
+    for cap in (1, 2, 3, 4, 5, 20):
+        ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, 1, cap)
+        for nm, kw in [("default", {})] + other_paths(C, L, rule):
+            out, it = dev_retrieve(Wd, C, L, V0, rule, 1, cap, **kw)
+            check_same(out, it, ref, itref, f"{rule} M={M} cap={cap} {nm}")
+        seen_capped += int((itref < 0).sum())
+        if cap == 20:
+            erased_part_dead = (ref.reshape(len(ref), C, L).sum(axis=2) == 0).any(axis=1)
+            seen_dead_late += int((erased_part_dead & (itref >= 3)).sum())
+    assert seen_capped > 0 and seen_dead_late > 0, "the sample must hold capped probes and probes that lose a cluster late"
+
+
 def test_edge_cases(networks):
     C, L, M = 8, 256, 20000
     msgs, Wo, Wd = networks(C, L, M)
