@@ -84,9 +84,11 @@ __device__ __forceinline__ bool some_group_empty(const Ctx<NW> &x, int t, uint64
 // entries are taken, whole words at a time and in order; what is taken is cleared from pw[] and
 // summask[], so that calling again continues where this chunk stopped.  Returns the entry count; or -1,
 // as soon as the set bits of pw[] are seen to number more than give_up (pw[], list are then unusable).
+// first_rank, if given, receives per slot the list position of the first bit of this lane's word
+// (meaningful where the word was taken).
 template <int NW>
 __device__ __forceinline__ int take_chunk(const Ctx<NW> &x, uint32_t (&pw)[NW], uint64_t (&summask)[NW],
-                                          uint32_t &list, int give_up = 1 << 30)
+                                          uint32_t &list, int give_up = 1 << 30, uint32_t *first_rank = nullptr)
 {
     int base = 0;
     bool open = true;  // false once something had to be left for the next chunk
@@ -98,36 +100,51 @@ __device__ __forceinline__ int take_chunk(const Ctx<NW> &x, uint32_t (&pw)[NW], 
         uint64_t mk = ballot(pc > 0u);
         if (mk) {
             // rank of this lane's first bit = bits in lower lanes = sum over k of #(lower lanes with > k bits)
-            uint32_t rank = (uint32_t)base;
-            int tot = 0;
-            for (uint32_t k = 1; mk; ++k) {
-                rank += mbcnt(mk);
-                tot += __builtin_popcountll(mk);
-                mk = ballot(pc > k);
-            }
-            if (base + tot > give_up) return -1;
-            uint32_t w = pw[t];
-            if (base + tot > kListMax) {
-                // keep the words that fit entirely; the rest of this slot and all later slots wait
-                const bool fits = rank + pc <= (uint32_t)kListMax;
-                w = fits ? w : 0u;
-                tot = 0;
-                mk = ballot(w != 0u);
-                for (uint32_t k = 1; mk; ++k) {
-                    tot += __builtin_popcountll(mk);
-                    mk = ballot(fits && pc > k);
-                }
-                open = false;
-            }
-            pw[t] &= ~w;
-            base += tot;
-            while (ballot(w != 0u)) {
-                const bool has = (w != 0u);
-                const uint32_t j = x.bit0[t] + (uint32_t)__builtin_ctz(w | 0x80000000u);
-                // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
+            uint32_t rank = (uint32_t)base + mbcnt(mk);
+            int tot = __builtin_popcountll(mk);
+            mk = ballot(pc > 1u);
+            if (NW == 1 && !mk && base + tot <= kListMax) {
+                // the common case, every listed word holds one bit: one round of pushes (kept to one word
+                // per lane: with more slots the extra path costs registers the kernels do not have)
+                if (base + tot > give_up) return -1;
+                if (first_rank) first_rank[t] = rank;
+                const bool has = pc > 0u;
+                const uint32_t j = x.bit0[t] + (uint32_t)__builtin_ctz(pw[t] | 0x80000000u);
                 list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2), (int)(has ? j + 1u : 0u));
-                w &= w - 1u;
-                ++rank;
+                pw[t] = 0u;
+                base += tot;
+            } else {
+                for (uint32_t k = 2; mk; ++k) {
+                    rank += mbcnt(mk);
+                    tot += __builtin_popcountll(mk);
+                    mk = ballot(pc > k);
+                }
+                if (base + tot > give_up) return -1;
+                if (first_rank) first_rank[t] = rank;
+                uint32_t w = pw[t];
+                if (base + tot > kListMax) {
+                    // keep the words that fit entirely; the rest of this slot and all later slots wait
+                    const bool fits = rank + pc <= (uint32_t)kListMax;
+                    w = fits ? w : 0u;
+                    tot = 0;
+                    mk = ballot(w != 0u);
+                    for (uint32_t k = 1; mk; ++k) {
+                        tot += __builtin_popcountll(mk);
+                        mk = ballot(fits && pc > k);
+                    }
+                    open = false;
+                }
+                pw[t] &= ~w;
+                base += tot;
+                while (ballot(w != 0u)) {
+                    const bool has = (w != 0u);
+                    const uint32_t j = x.bit0[t] + (uint32_t)__builtin_ctz(w | 0x80000000u);
+                    // forward permute: lane `rank` receives j+1; idle lanes all push 0 to lane 63
+                    list |= (uint32_t)__builtin_amdgcn_ds_permute((int)((has ? rank : 63u) << 2),
+                                                                  (int)(has ? j + 1u : 0u));
+                    w &= w - 1u;
+                    ++rank;
+                }
             }
         }
         const uint64_t sm = summask[t];
@@ -400,10 +417,11 @@ __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (
 // fields; no further rows are fetched and no lists built.  Each candidate's row is fetched once, to
 // fill A: lane q takes bit j_q of row j_q' from the lane that holds that word (ds_bpermute).
 // On entry p = 1 passes are done; on exit v holds the final vector and the return value is the
-// iteration count to report.  `list` / T come from take_chunk over the candidates.
+// iteration count to report.  `list` / T / first_rank come from take_chunk over the candidates cand[].
 template <int NW, int RULE, int LG>
-__device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t (&probe)[NW], uint32_t list, int T,
-                                                int max_iters, uint32_t (&v)[NW])
+__device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t (&probe)[NW],
+                                                const uint32_t (&cand)[NW], const uint32_t (&first_rank)[NW],
+                                                uint32_t list, int T, int max_iters, uint32_t (&v)[NW])
 {
     const bool inl = x.lane < T;
     const uint32_t jlast = readlane(list, T - 1) - 1u;
@@ -459,17 +477,19 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
         }
     }
 
-    // final vector: the probe's known neurons (unless switched off) and the candidates still on
+    // final vector: the probe's known neurons (unless switched off) and the candidates still on.  The
+    // candidates of a word sit at consecutive list positions from first_rank on, lowest bit first.
 #pragma unroll
-    for (int u = 0; u < NW; ++u) v[u] = known_on ? probe[u] : 0u;
-    while (m) {
-        const int q = __builtin_ctz(m);
-        m &= m - 1u;
-        const uint32_t j = readlane(jq, q);
-        const uint32_t w = j >> 5;
-#pragma unroll
-        for (int u = 0; u < NW; ++u)
-            if ((w >> 6) == (uint32_t)u && (uint32_t)x.lane == (w & 63u)) v[u] |= 1u << (j & 31u);
+    for (int u = 0; u < NW; ++u) {
+        uint32_t out = known_on ? probe[u] : 0u;
+        uint32_t w = cand[u], pos = first_rank[u];
+        while (ballot(w != 0u)) {
+            const uint32_t low = w & (0u - w);
+            out |= ((m >> (pos & 31u)) & 1u) ? low : 0u;
+            w ^= low;
+            ++pos;
+        }
+        v[u] = out;
     }
     return it;
 }
@@ -616,9 +636,15 @@ k_retrieve_wave(RetrieveArgs a)
                                __builtin_popcountll(ballot((pw[t] & (pw[t] - 1u)) != 0u));
                 if (!multi && !lost && !bare && nz == known && atleast <= 32) {
                     uint32_t list;
-                    const int T = take_chunk(x, pw, summask, list, 32);
+                    uint32_t cand[NW], first_rank[NW];
+#pragma unroll
+                    for (int t = 0; t < NW; ++t) {
+                        cand[t] = pw[t];
+                        first_rank[t] = 0u;
+                    }
+                    const int T = take_chunk(x, pw, summask, list, 32, first_rank);
                     if (T >= 1) {
-                        it = candidate_passes<NW, RULE, LG>(x, probe, list, T, a.max_iters, v);
+                        it = candidate_passes<NW, RULE, LG>(x, probe, cand, first_rank, list, T, a.max_iters, v);
                         finished = true;
                     }
                 }
