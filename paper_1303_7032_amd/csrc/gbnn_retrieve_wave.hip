@@ -414,8 +414,8 @@ __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (
 // run of lanes) and A = its adjacency over the candidates, bit q' = w between candidates q' and q;
 // bits of its own cluster are ones (the table's intra-cluster blocks are all ones).  A pass is then
 // "does A & alive have a bit in every cluster's run of positions", a zero-field test with the runs as
-// fields; no further rows are fetched and no lists built.  Each candidate's row is fetched once, to
-// fill A: lane q takes bit j_q of row j_q' from the lane that holds that word (ds_bpermute).
+// fields; no further rows are fetched and no lists built.  A is filled by T gathers: for every
+// candidate q' one load in which lane q reads the word of row j_q' that holds bit j_q.
 // On entry p = 1 passes are done; on exit v holds the final vector and the return value is the
 // iteration count to report.  `list` / T / first_rank come from take_chunk over the candidates cand[].
 template <int NW, int RULE, int LG>
@@ -432,27 +432,19 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
     const uint32_t maskT = T == 32 ? 0xFFFFFFFFu : (1u << T) - 1u;
     const uint32_t S = (uint32_t)ballot(inl && cq != below);          // first position of every cluster's run
     const uint32_t E = ((S >> 1) | (1u << (T - 1))) & maskT;          // last position of every run
-    const uint32_t wq = jq >> 5;                                      // word of the candidate: slot wq / 64, lane wq % 64
-    const uint32_t waddr = (wq & 63u) << 2;
+    const uint32_t woff = (jq >> 5) << 2;                             // byte offset of the candidate's word in a row
     const uint32_t bitpos = jq & 31u;
     const uint32_t offv = __umul24(jq, x.rowbytes);
 
+    // A: lane q reads, from the row of every candidate q', the one word that holds its own bit
     uint32_t A = 0u;
     for (int i0 = 0; i0 < T; i0 += 4) {
-        uint32_t r[4][NW];
+        uint32_t w[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+        for (int q = 0; q < 4; ++q) w[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, woff, readlane(offv, i0 + q), 0);
         uint32_t t = 0u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((int)waddr, (int)r[q][0]);
-#pragma unroll
-            for (int u = 1; u < NW; ++u) {
-                const uint32_t wu = (uint32_t)__builtin_amdgcn_ds_bpermute((int)waddr, (int)r[q][u]);
-                w = (wq >> 6) == (uint32_t)u ? wu : w;
-            }
-            t |= ((w >> bitpos) & 1u) << q;
-        }
+        for (int q = 0; q < 4; ++q) t |= ((w[q] >> bitpos) & 1u) << q;
         A |= t << i0;
     }
 
@@ -613,7 +605,7 @@ k_retrieve_wave(RetrieveArgs a)
             // in every erased cluster) finishes on the candidates' adjacency matrix; any other probe, and
             // a probe whose pass 1 changed nothing, takes the general loop below.
             bool finished = false;
-            if (NW == 1 && changed) {  // (with more words per lane filling the matrix costs what it saves)
+            if (changed) {
                 uint64_t multi = 0, lost = 0, bare = 0;
                 int nz = 0, known = 0;
                 uint32_t pw[NW];
