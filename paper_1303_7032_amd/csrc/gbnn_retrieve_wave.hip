@@ -242,6 +242,7 @@ __device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, uint32_t (&pw)
         // General case, branch-free: R collects the OR of the current cluster's rows; at the first
         // row of the next cluster (keep == 0) it is ANDed into acc and restarted.
         const uint32_t keepv = isfirst ? 0u : 0xFFFFFFFFu;
+        const uint64_t starts = ballot(isfirst);  // entries that begin a cluster (lanes past the end repeat the last entry)
         while (i0 < total) {
             if (total - i0 > 4) {
                 or_and_batch<NW, 8>(x, offv, keepv, i0, R, acc);
@@ -249,6 +250,17 @@ __device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, uint32_t (&pw)
             } else {
                 or_and_batch<NW, 4>(x, offv, keepv, i0, R, acc);
                 i0 += 4;
+            }
+            // Dense networks list tens of rows per cluster.  Once the OR of the cluster in progress covers
+            // everything still on, its remaining rows cannot switch anything off: skip to the next cluster.
+            if (i0 < total && !((starts >> i0) & 1ull)) {
+                uint64_t uncovered = 0;
+#pragma unroll
+                for (int u = 0; u < NW; ++u) uncovered |= ballot((acc[u] & ~R[u]) != 0u);
+                if (!uncovered) {
+                    const uint64_t later = starts >> i0;
+                    i0 = later ? i0 + __builtin_ctzll(later) : total;
+                }
             }
         }
         if (!rest) break;
