@@ -23,7 +23,6 @@
 // Passes are numbered alike for both probes of a wave; a probe that has converged lists no rows and
 // keeps its state while the other one finishes.  Per-probe scalars (row counts, flags, pass counts)
 // are pairs of wave-uniform values, turned into lane masks where a lane needs "the one of my half".
-#include <cstdlib>
 
 #include "gbnn_device.h"
 #include "gbnn_internal.h"

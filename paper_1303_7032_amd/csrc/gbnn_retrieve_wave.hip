@@ -25,7 +25,6 @@
 // are DPP butterflies over the lanes of a group, the listing of active neurons ranks set bits with
 // ballot + mbcnt and pushes their indices to lane `rank` with ds_permute, and the row loop is one
 // v_readlane plus one buffer_load (row offset in the scalar-offset operand) per row.
-#include <cstdlib>
 
 #include "gbnn_device.h"
 #include "gbnn_internal.h"
@@ -524,11 +523,11 @@ k_retrieve_wave(RetrieveArgs a)
         x.bit0[t] = (uint32_t)(t * 64 + x.lane) << 5;
         x.validmask[t] = ballot(x.valid[t]);
     }
-    const int wpb = (int)(blockDim.x >> 6);  // waves per workgroup
-    const int64_t wave = (int64_t)blockIdx.x * wpb + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t nwaves = (int64_t)gridDim.x * wpb;
-
-    for (int64_t k = wave; k < a.K; k += nwaves) {
+    // One probe per wave: the hardware's workgroup dispatcher balances the uneven probe times (a grid of
+    // resident waves striding over the probes measured 1.1-2x slower).
+    const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (k >= a.K) return;
+    {
         // ---- probe load: 32 bytes per word, packed to bits; or one symbol per cluster
         uint32_t v[NW];
         if (a.sym_in) {
@@ -760,18 +759,9 @@ k_retrieve_wave(RetrieveArgs a)
 template <int NW, int LG>
 hipError_t launch_one(const RetrieveArgs &a, hipStream_t s)
 {
-    int wpb = 4;
-    if (const char *e = std::getenv("GBNN_BLOCK_WAVES")) {  // tuning aid
-        const long v = std::atol(e);
-        if (v >= 1 && v <= 4) wpb = (int)v;
-    }
-    int64_t blocks = (a.K + wpb - 1) / wpb;
-    int64_t cap = 1 << 20;
-    if (const char *e = std::getenv("GBNN_GRID_BLOCKS")) {  // tuning aid
-        const long v = std::atol(e);
-        if (v > 0) cap = v;
-    }
-    if (blocks > cap) blocks = cap;
+    const int wpb = 4;  // waves per workgroup
+    const int64_t blocks = (a.K + wpb - 1) / wpb;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(64 * wpb);
     switch (a.rule) {
     case GBNN_SUM_OF_SUM:
