@@ -500,7 +500,7 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
 // Register budget: 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per lane (2 for sum-of-sum at 4).
 template <int NW, int RULE, int LG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? 5 : RULE == GBNN_SUM_OF_SUM ? 2 : 4))) void
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : RULE == GBNN_SUM_OF_MAX ? 5 : 4))) void
 k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
