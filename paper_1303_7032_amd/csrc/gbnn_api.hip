@@ -34,6 +34,33 @@ int pick_path(int C, int L, const void *V0, const void *Vout)
     return wave_words_per_lane(C, L);
 }
 
+// Checks common to both boundaries, then the launch.
+int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K, int rule, int gamma, int max_iters,
+                    int32_t *iters_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, (C * L + 31) / 32))
+        return GBNN_ERR_WORKSPACE;
+    if (K == 0) return GBNN_OK;
+    a.W = W;
+    a.nw = (C * L + 31) / 32;
+    a.Wb = static_cast<const uint32_t *>(workspace);
+    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
+    a.iters = iters_out;
+    a.K = K;
+    a.C = C;
+    a.L = L;
+    a.n = C * L;
+    a.rule = rule;
+    a.gamma = gamma;
+    a.max_iters = max_iters;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int path = pick_path(C, L, a.V0, a.Vout);
+    const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
+                         : path            ? launch_retrieve_wave(a, path, s)
+                                           : launch_retrieve_generic(a, s);
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -76,33 +103,6 @@ int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t worksp
     const hipError_t e =
         launch_prepare(W, C, L, nw, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
                        reinterpret_cast<uint32_t *>(ws), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
-}
-
-// Checks common to both boundaries, then the launch.
-static int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K, int rule, int gamma,
-                           int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes, void *stream)
-{
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < gbnn_workspace_bytes(C, L, K, rule))
-        return GBNN_ERR_WORKSPACE;
-    if (K == 0) return GBNN_OK;
-    a.W = W;
-    a.nw = (int)gbnn_w_row_words(C, L);
-    a.Wb = static_cast<const uint32_t *>(workspace);
-    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
-    a.iters = iters_out;
-    a.K = K;
-    a.C = C;
-    a.L = L;
-    a.n = C * L;
-    a.rule = rule;
-    a.gamma = gamma;
-    a.max_iters = max_iters;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int path = pick_path(C, L, a.V0, a.Vout);
-    const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
-                         : path            ? launch_retrieve_wave(a, path, s)
-                                           : launch_retrieve_generic(a, s);
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
