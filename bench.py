@@ -116,10 +116,13 @@ def main() -> int:
                        "hbm_GBs": abytes / (ms.mean() * 1e-3) / 1e9}
     dominant = max(rules, key=lambda r: per_rule[r]["ms_avg"])
     achieved = per_rule[dominant]["hbm_GBs"]
-    traffic = None
+    # HBM-side bytes per launch of the dominant kernel, from rocprofv3 counter runs kept under profiles/
+    traffic = traffic_detail = None
     tfile = ROOT / "profiles" / "hbm_traffic.json"
     if tfile.exists():
-        traffic = json.loads(tfile.read_text()).get(f"{args.workload}:{dominant}")
+        traffic_detail = json.loads(tfile.read_text()).get(f"{args.workload}:{dominant}")
+        if traffic_detail:
+            traffic = traffic_detail["total_bytes"]
 
     # ---- reference points after the timed region: a plain device copy of the probe tensor (what the memory
     # system gives a kernel that only reads K*n bytes and writes K*n bytes), and the same retrieval with
@@ -212,14 +215,15 @@ def main() -> int:
                   else f"retrieved queries/sec at c={C},l={L} ({', '.join(rules)})",
         "value": value, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8 activity in/out, 1-bit packed W and state, u32 bitwise/integer arithmetic",
+        "dtype": "u32",  # bitwise / integer arithmetic on 32-bit words of packed bits (activity crosses the boundary as u8)
         "data": "synthetic",
         "config": {"workload": f"{w.name}: C={C} L={L} n={n} M={w.M} K={K} erased={w.e} cap={w.max_iters} "
                                f"rules={'+'.join(rules)} (one step = one gbnn_retrieve per rule over the batch)",
                    "queries_per_step": queries_per_step, "seed": w.seed, "density": w.density(),
                    "kernel_path": gb.gbnn_retrieve_path(C, L, rules[0], V0d, outs[rules[0]])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": f"gbnn_retrieve[{dominant}]",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": traffic_detail,
+                     "kernel": f"gbnn_retrieve[{dominant}]",
                      "algorithmic_bytes_per_launch": abytes,
                      "device_copy_GBs_same_run": copy_GBs, "frac_of_device_copy": achieved / copy_GBs},
         "cpu_baseline": cpu,
