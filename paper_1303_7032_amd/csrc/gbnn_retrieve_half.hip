@@ -78,9 +78,10 @@ __device__ __forceinline__ uint32_t entry(uint32_t listv, uint32_t addr)
 // bits of its lanes' pw (row = neuron index, ascending) followed by one summary row (row n + c) for
 // every lane flagged in summask (the first lane of a fully active cluster c).  At most kHalfListMax
 // entries per half are taken, in order; what is taken is cleared from pw and summask, so that
-// calling again continues where this chunk stopped.  tot0 / tot1 = entries taken.
+// calling again continues where this chunk stopped.  tot0 / tot1 = entries taken.  first_rank, if
+// given, receives the list position (within the half) of the first bit of this lane's word.
 __device__ __forceinline__ void take_chunk_h(const HCtx &x, uint32_t &pw, uint64_t &summask, uint32_t &list,
-                                             uint32_t &tot0, uint32_t &tot1)
+                                             uint32_t &tot0, uint32_t &tot1, uint32_t *first_rank = nullptr)
 {
     constexpr uint32_t kMax = (uint32_t)kHalfListMax;
     list = 0u;
@@ -98,6 +99,7 @@ __device__ __forceinline__ void take_chunk_h(const HCtx &x, uint32_t &pw, uint64
             mk = ballot(pc > k);
         }
         rank -= t0 & x.upperm;
+        if (first_rank) *first_rank = rank;
         // every lane pushes its bits, lowest first, while their ranks are below the limit
         uint32_t w = pw;
         for (;;) {
@@ -347,6 +349,104 @@ __device__ __forceinline__ uint32_t signals_equal_h(const HCtx &x, uint32_t v, u
     return eq;
 }
 
+// The passes after the first on the adjacency matrices of the candidates, for both probes of the wave
+// (the method of the one-wave-per-probe kernel: there a probe qualifies when every known cluster holds
+// one active neuron, all still on after pass 1, and pass 1 left a few candidates in every erased
+// cluster).  Lane q of a half holds candidate q of its probe and A, its adjacency over that probe's
+// candidates, filled by gathers: for candidate q' one load in which lane q reads the word of row j_q'
+// that holds bit j_q, the row offset coming from the half's list.  A pass is the zero-field test of
+// A & alive over the clusters' runs of list positions.  live0 / live1: the probe still runs after
+// pass 1 (else it is finished: it keeps `fin` and reports 1 pass).  On exit v is the final vector.
+template <int RULE, int LGL>
+__device__ __forceinline__ void candidate_passes_h(const HCtx &x, uint32_t probe, uint32_t cand, uint32_t first_rank,
+                                                   uint32_t list, uint32_t T0, uint32_t T1, bool live0, bool live1,
+                                                   uint32_t fin, int max_iters, uint32_t &v, int &it0, int &it1)
+{
+    const uint32_t Tv = x.mine(T0, T1);
+    const bool inl = x.gl < Tv;
+    const uint32_t last = entry(list, x.basev + ((Tv - 1u) << 2));      // (garbage when Tv == 0: not used then)
+    const uint32_t jq = (inl ? list : (Tv ? last : 1u)) - 1u;            // lanes past the end repeat the last candidate
+    const uint32_t cq = jq >> (LGL + 5);
+    const uint32_t below = (uint32_t)__builtin_amdgcn_update_dpp((int)0xFFFFFFFFu, (int)cq, 0x138 /* wave_shr:1 */, 0xf,
+                                                                 0xf, false);
+    const uint64_t startm = ballot(inl && (x.gl == 0u || cq != below));  // first position of every cluster's run
+    const uint32_t S0 = lo32(startm), S1 = hi32(startm);
+    const uint32_t full0 = (1u << T0) - 1u, full1 = (1u << T1) - 1u;     // T <= kHalfListMax < 32
+    const uint32_t E0 = T0 ? ((S0 >> 1) | (1u << (T0 - 1u))) & full0 : 0u;  // last position of every run
+    const uint32_t E1 = T1 ? ((S1 >> 1) | (1u << (T1 - 1u))) & full1 : 0u;
+    const uint32_t woff = (jq >> 5) << 2;
+    const uint32_t bitpos = jq & 31u;
+    const uint32_t offv = __umul24(jq, x.rowbytes);
+    const uint32_t Tmax = T0 > T1 ? T0 : T1;
+
+    uint32_t A = 0u;
+    uint32_t addr = x.basev;
+    for (uint32_t i0 = 0; i0 < Tmax; i0 += 4u, addr += 16u) {
+        uint32_t e[4], w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = entry(offv, addr + 4u * q);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[q] = __builtin_amdgcn_raw_buffer_load_b32(x.rsrc, e[q] + woff, 0, 0);
+        uint32_t t = 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t |= ((w[q] >> bitpos) & 1u) << q;
+        A |= t << i0;
+    }
+
+    uint32_t m0 = live0 ? full0 : 0u, m1 = live1 ? full1 : 0u;  // candidates still on
+    bool kon0 = true, kon1 = true;                              // the known neurons (sum-of-max can switch them off)
+    bool chg0 = live0, chg1 = live1;
+    bool done0 = false, done1 = false;
+    const uint32_t Sv = x.mine(S0, S1), Ev = x.mine(E0, E1);
+    for (int p = 1;;) {
+        if (!done0 && (!chg0 || p == max_iters)) {
+            it0 = chg0 ? -p : p;
+            done0 = true;
+        }
+        if (!done1 && (!chg1 || p == max_iters)) {
+            it1 = chg1 ? -p : p;
+            done1 = true;
+        }
+        if (done0 && done1) break;
+        ++p;
+        const uint32_t y = A & x.mine(m0, m1);
+        const uint64_t offm = ballot(((y - Sv) & ~y & Ev) != 0u);
+        if (!done0) {
+            if (((m0 - S0) & ~m0 & E0) != 0u) {  // an erased cluster has no candidate left: nobody hears from it
+                chg0 = m0 != 0u || (RULE == GBNN_SUM_OF_MAX && kon0);
+                m0 = 0u;
+                if (RULE == GBNN_SUM_OF_MAX) kon0 = false;
+            } else {
+                chg0 = (m0 & lo32(offm)) != 0u;
+                m0 &= ~lo32(offm);
+            }
+        }
+        if (!done1) {
+            if (((m1 - S1) & ~m1 & E1) != 0u) {
+                chg1 = m1 != 0u || (RULE == GBNN_SUM_OF_MAX && kon1);
+                m1 = 0u;
+                if (RULE == GBNN_SUM_OF_MAX) kon1 = false;
+            } else {
+                chg1 = (m1 & hi32(offm)) != 0u;
+                m1 &= ~hi32(offm);
+            }
+        }
+    }
+
+    // final vector: the probe's known neurons (unless switched off) and the candidates still on; the
+    // candidates of a word sit at consecutive list positions from first_rank on, lowest bit first
+    uint32_t out = lane_of(halves(kon0, kon1)) ? probe : 0u;
+    const uint32_t mv = x.mine(m0, m1);
+    uint32_t w = cand, pos = first_rank;
+    while (ballot(w != 0u)) {
+        const uint32_t low = w & (0u - w);
+        out |= ((mv >> (pos & 31u)) & 1u) ? low : 0u;
+        w ^= low;
+        ++pos;
+    }
+    v = lane_of(halves(live0, live1)) ? out : fin;
+}
+
 // RULE = gbnn_rule, LGL = log2(lanes per cluster) = log2(L / 32).
 template <int RULE, int LGL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k_retrieve_half(RetrieveArgs a)
@@ -395,6 +495,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     if (RULE == GBNN_SUM_OF_MAX || RULE == GBNN_HYBRID) {
         // Erased clusters = clusters with no active neuron in the probe.
         const bool erased = x.valid && group_or<LGL>(v) == 0u;
+        const uint32_t probe = v;
         uint32_t acc, d;
         bool chg0 = true, chg1 = true;
         if (RULE == GBNN_SUM_OF_MAX) {
@@ -435,7 +536,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
             }
             // the stop test is made only after a bail-out-early pass (Algorithm 2, line 13)
         }
-        for (int p = 1;; ++p) {
+        // When both probes are the usual kind (or finished already) the remaining passes run on the
+        // candidates' adjacency matrices; otherwise both take the general loop below.
+        bool finished = false;
+        if (chg0 || chg1) {
+            const uint32_t pcp = __popc(probe);
+            const uint64_t nz = ballot(pcp > 0u), multi = ballot(pcp > 1u), knownm = ballot(x.islead && !erased);
+            const uint64_t lost = ballot(!erased && acc != probe);
+            const uint32_t cand = erased ? acc : 0u;
+            const uint64_t bare = ballot(erased && group_or<LGL>(cand) == 0u);
+            const uint64_t c1 = ballot(cand != 0u), c2 = ballot((cand & (cand - 1u)) != 0u);
+            const bool ok0 = !chg0 || (lo32(multi) == 0u && __popc(lo32(nz)) == __popc(lo32(knownm)) && lo32(lost) == 0u &&
+                                       lo32(bare) == 0u && __popc(lo32(c1)) + __popc(lo32(c2)) <= kHalfListMax);
+            const bool ok1 = !chg1 || (hi32(multi) == 0u && __popc(hi32(nz)) == __popc(hi32(knownm)) && hi32(lost) == 0u &&
+                                       hi32(bare) == 0u && __popc(hi32(c1)) + __popc(hi32(c2)) <= kHalfListMax);
+            if (ok0 && ok1) {
+                const uint32_t mine_cand = lane_of(halves(chg0, chg1)) ? cand : 0u;
+                uint32_t pw = mine_cand, list, T0, T1, first_rank = 0u;
+                uint64_t summask = 0;
+                take_chunk_h(x, pw, summask, list, T0, T1, &first_rank);
+                if (ballot(pw != 0u) == 0ull && (T0 >= 1u || !chg0) && (T1 >= 1u || !chg1)) {
+                    candidate_passes_h<RULE, LGL>(x, probe, mine_cand, first_rank, list, T0, T1, chg0, chg1, acc,
+                                                  a.max_iters, v, it0, it1);
+                    finished = true;
+                }
+            }
+        }
+        for (int p = 1; !finished; ++p) {
             v = acc;
             if (!done0 && (!chg0 || p == a.max_iters)) {
                 it0 = chg0 ? -p : p;
