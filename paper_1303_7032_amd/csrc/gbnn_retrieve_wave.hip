@@ -270,6 +270,55 @@ __device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, uint32_t (&pw)
     for (int u = 0; u < NW; ++u) acc[u] &= R[u];
 }
 
+// The same update as fetch_and_apply for crowded clusters (dense networks: tens of active neurons per
+// cluster, most lanes of a cluster holding some), without building a list: cluster by cluster, every
+// lane of the cluster offers the row of its lowest remaining bit (a lane with none offers the all-zero
+// row), the rows of all its lanes are fetched together and ORed into R, and the next round takes the
+// next bits -- until R covers every neuron still on (then the rest of the cluster cannot switch
+// anything off) or no bits remain.  Needs clusters of at least 4 lanes.  pw[] is consumed.
+template <int NW, int LG>
+__device__ __forceinline__ void apply_by_cluster(const Ctx<NW> &x, uint32_t (&pw)[NW], uint32_t (&acc)[NW])
+{
+    static_assert(LG >= 2, "clusters of at least 4 lanes");
+    constexpr int LW = 1 << LG;        // lanes per cluster
+    constexpr int B = LW < 8 ? LW : 8;  // rows fetched together
+    const uint32_t zero_off = __umul24(x.nrows + x.nclusters, x.rowbytes);
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        const uint32_t cluster_bits = group_or<LG>(pw[t]);  // (all lanes take part in the butterfly)
+        uint64_t todo = ballot(x.islead[t] && cluster_bits != 0u);  // first lanes of the clusters to walk
+        while (todo) {
+            const int lead = __builtin_ctzll(todo);
+            todo &= todo - 1ull;
+            uint32_t R[NW];
+#pragma unroll
+            for (int u = 0; u < NW; ++u) R[u] = 0u;
+            uint32_t w = ((x.lane ^ lead) >> LG) == 0 ? pw[t] : 0u;  // this cluster's lanes
+            for (;;) {
+                const uint32_t offv = w ? __umul24(x.bit0[t] + (uint32_t)__builtin_ctz(w), x.rowbytes) : zero_off;
+                w &= w - 1u;  // (0 stays 0)
+#pragma unroll
+                for (int b0 = 0; b0 < LW; b0 += B) {
+                    uint32_t r[B][NW];
+#pragma unroll
+                    for (int q = 0; q < B; ++q) load_row(x, x.wbrsrc, readlane(offv, lead + b0 + q), r[q]);
+#pragma unroll
+                    for (int q = 0; q < B; ++q)
+#pragma unroll
+                        for (int u = 0; u < NW; ++u) R[u] |= r[q][u];
+                }
+                if (!ballot(w != 0u)) break;
+                uint64_t uncovered = 0;
+#pragma unroll
+                for (int u = 0; u < NW; ++u) uncovered |= ballot((acc[u] & ~R[u]) != 0u);
+                if (!uncovered) break;
+            }
+#pragma unroll
+            for (int u = 0; u < NW; ++u) acc[u] &= R[u];
+        }
+    }
+}
+
 // One sum-of-max pass from the second on.  d[] is nonzero in the lanes that changed in the previous
 // pass; only the clusters holding such a lane ("dirty") can switch anything off (Lemma 1).
 //   acc = v AND over dirty clusters c' of (OR of the rows of the active neurons of c' | own mask of c')
@@ -289,11 +338,24 @@ __device__ __forceinline__ void som_step(const Ctx<NW> &x, const uint32_t (&v)[N
     }
     uint32_t pw[NW];
     uint64_t summask[NW];
+    int holders = 0, dirty_lanes = 0;  // lanes of dirty clusters with an active neuron / all lanes of dirty clusters
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
+        const bool dirty = group_or<LG>(d[t]) != 0u;
         acc[t] = v[t];
-        pw[t] = group_or<LG>(d[t]) ? v[t] : 0u;
+        pw[t] = dirty ? v[t] : 0u;
         summask[t] = 0;
+        if (LG >= 2) {
+            holders += __builtin_popcountll(ballot(pw[t] != 0u));
+            dirty_lanes += __builtin_popcountll(ballot(dirty && x.valid[t]));
+        }
+    }
+    if constexpr (LG >= 2) {
+        // crowded clusters (3 of 4 lanes hold active neurons): walk them lane by lane instead of listing
+        if (4 * holders >= 3 * dirty_lanes && holders > 8) {
+            apply_by_cluster<NW, LG>(x, pw, acc);
+            return;
+        }
     }
     fetch_and_apply<NW, LG>(x, pw, summask, acc);
 }
