@@ -82,7 +82,8 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
  * a copy of W whose intra-cluster blocks are all ones (so that "OR of the rows of the active
  * neurons of cluster c', or the neuron is itself in c'" -- the bail-out-early test of Section
  * IV-D -- is a plain OR of rows), and one summary row per cluster, the OR of its L rows (what a
- * fully active cluster, i.e. an erased cluster at the start of sum-of-max, contributes).
+ * fully active cluster, i.e. an erased cluster at the start of sum-of-max, contributes), with a
+ * flag per cluster telling whether that row is all ones (it then changes nothing and is skipped).
  * Call it after W changes (gbnn_store) and before gbnn_retrieve; the workspace then serves any
  * number of gbnn_retrieve calls on that W, of any rule and batch size up to the K it was sized
  * for.  It depends only on W, C and L.

@@ -45,6 +45,7 @@ int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K,
     a.nw = (C * L + 31) / 32;
     a.Wb = static_cast<const uint32_t *>(workspace);
     a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
+    a.full = reinterpret_cast<const uint64_t *>(static_cast<const char *>(workspace) + workspace_full_offset(C, L, a.nw));
     a.iters = iters_out;
     a.K = K;
     a.C = C;
@@ -102,7 +103,8 @@ int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t worksp
     char *ws = static_cast<char *>(workspace);
     const hipError_t e =
         launch_prepare(W, C, L, nw, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
-                       reinterpret_cast<uint32_t *>(ws), static_cast<hipStream_t>(stream));
+                       reinterpret_cast<uint32_t *>(ws), reinterpret_cast<uint64_t *>(ws + workspace_full_offset(C, L, nw)),
+                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 

@@ -15,6 +15,7 @@ struct RetrieveArgs {
     const uint32_t *W;    // canonical adjacency, uint32[n][nw]
     const uint32_t *Wb;   // W with all-one intra-cluster blocks, uint32[n][nw], followed directly by
     const uint32_t *has;  // the cluster summaries, uint32[C][nw]: bit i of row c' = "i is in c' or adjacent to a neuron of c'"
+    const uint64_t *full; // one word: bit c' set = the summary row of c' is all ones (ANDing it changes nothing)
     const uint8_t *V0;    // uint8[K][n]                       } the activity boundary (gbnn_retrieve);
     uint8_t *Vout;        // uint8[K][n]                       } both nullptr at the message boundary
     const int32_t *sym_in;  // int32[K][C] or nullptr: the message boundary (gbnn_retrieve_symbols) when set
@@ -32,10 +33,12 @@ struct RetrieveArgs {
 // that one buffer resource reaches all of it.
 constexpr int kTableExtraRows = 2;  // the all-zero and the all-one row
 inline size_t workspace_has_offset(int C, int L, int nw) { return (size_t)C * L * nw * sizeof(uint32_t); }
-inline size_t workspace_total_bytes(int C, int L, int nw)
+// ... followed, at the next multiple of 256 bytes, by one uint64: bit c set = summary row c is all ones.
+inline size_t workspace_full_offset(int C, int L, int nw)
 {
     return (((size_t)C * L + C + kTableExtraRows) * nw * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
+inline size_t workspace_total_bytes(int C, int L, int nw) { return workspace_full_offset(C, L, nw) + 256; }
 
 // Which kernel family serves a shape.  One wavefront per probe: packed words per lane (1, 2, 4), 0 = not
 // served.  Half a wavefront per probe (two probes per wave, one word per lane): yes or no.
@@ -44,7 +47,8 @@ bool half_wave_serves(int C, int L);
 
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
                         hipStream_t s);
-hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, hipStream_t s);
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
+                          hipStream_t s);
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);
 hipError_t launch_retrieve_half(const RetrieveArgs &a, hipStream_t s);
 hipError_t launch_retrieve_generic(const RetrieveArgs &a, hipStream_t s);

@@ -502,7 +502,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
             // Section III-C: erased clusters start fully active.  Pass 1: the known clusters contribute
             // the rows of their active neurons, the (fully active) erased clusters their summary rows.
             uint32_t pw = v;
-            uint64_t summask = ballot(erased && x.islead);
+            const uint64_t full = *a.full;  // clusters whose summary row is all ones: it changes nothing, not fetched
+            uint64_t summask = ballot(erased && x.islead && !((full >> (x.myc & 63u)) & 1ull));
             if (erased) v = 0xFFFFFFFFu;
             acc = v;
             fetch_and_apply_h<LGL>(x, pw, summask, acc);

@@ -625,10 +625,12 @@ k_retrieve_wave(RetrieveArgs a)
                 // their summary rows.
                 uint32_t pw[NW];
                 uint64_t summask[NW];
+                const uint64_t full = *a.full;
 #pragma unroll
                 for (int t = 0; t < NW; ++t) {
                     pw[t] = v[t];
-                    summask[t] = ballot(erased[t] && x.islead[t]);
+                    // (a summary row that is all ones changes nothing: not fetched)
+                    summask[t] = ballot(erased[t] && x.islead[t] && !((full >> (x.myc[t] & 63u)) & 1ull));
                     if (erased[t]) v[t] = 0xFFFFFFFFu;
                     acc[t] = v[t];
                 }

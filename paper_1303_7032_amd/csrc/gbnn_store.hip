@@ -75,6 +75,26 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
     }
 }
 
+// full = bit c set iff the summary row of cluster c has every neuron's bit: then every neuron has a
+// neighbour in c (or is in c), and a fully active cluster c switches nobody off.  One wave; lane c checks
+// row c.  With the densities the method works at this is the rule, and retrieval skips those rows.
+__global__ __launch_bounds__(64) void k_summary_full(const uint32_t *__restrict__ has, int C, int n, int nw,
+                                                     uint64_t *__restrict__ full)
+{
+    const int c = threadIdx.x;
+    bool all = c < C;
+    if (c < C) {
+        const uint32_t *row = has + (int64_t)c * nw;
+        for (int w = 0; w < nw; ++w) {
+            const int bits = n - 32 * w;  // neurons in this word
+            const uint32_t need = bits >= 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+            all = all && (row[w] & need) == need;
+        }
+    }
+    const uint64_t m = __ballot(all);
+    if (c == 0) *full = m;
+}
+
 // Wb = W with the intra-cluster blocks set to all ones: row j gets the bits of j's own cluster.
 // Also fills the all-zero row `zero_row` of the table and the all-one row that follows it.
 __global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict__ W, int L, int nw, int64_t words,
@@ -105,11 +125,15 @@ hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, 
     return hipGetLastError();
 }
 
-hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, hipStream_t s)
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
+                          hipStream_t s)
 {
     dim3 grid((unsigned)((nw + 63) / 64), (unsigned)C);
     hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
     hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(64), 0, s, has, C, C * L, nw, full);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t words = (int64_t)C * L * nw;
     int64_t blocks = (words + 255) / 256;

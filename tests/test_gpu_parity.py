@@ -138,6 +138,9 @@ SHAPES = [
     (2, 512, 30000, 1, 67),    # ... a cluster is half of the half-wave
     (32, 64, 3000, 16, 131),   # 64 words, two per cluster: one wave per probe
     (64, 32, 1000, 32, 45),    # 64 one-word clusters
+    (8, 256, 300, 4, 130),     # a nearly empty network: no cluster summary is all ones (none may be skipped)
+    (8, 128, 100, 5, 131),     # ... two probes per wave
+    (8, 256, 3000, 4, 130),    # ... some summaries all ones, some not
 ]
 
 
