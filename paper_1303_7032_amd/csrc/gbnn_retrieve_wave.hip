@@ -426,50 +426,47 @@ template <int NW, int LG>
 __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (&v)[NW], int target, uint32_t (&eq)[NW])
 {
     constexpr int D = 7;
-    uint32_t pl[D][NW], ovf[NW];
+    // One slot of words at a time (the rows are listed again for every slot): this path is rare, and
+    // counters for all slots at once would set the register budget of the whole kernel.
 #pragma unroll
     for (int u = 0; u < NW; ++u) {
-        ovf[u] = 0u;
+        uint32_t pl[D], ovf = 0u;
 #pragma unroll
-        for (int q = 0; q < D; ++q) pl[q][u] = 0u;
-    }
-    uint32_t pw[NW];
-    uint64_t summask[NW];
+        for (int q = 0; q < D; ++q) pl[q] = 0u;
+        uint32_t pw[NW];
+        uint64_t summask[NW];
 #pragma unroll
-    for (int t = 0; t < NW; ++t) {
-        pw[t] = v[t];
-        summask[t] = 0;
-    }
-    for (;;) {
-        uint32_t list;
-        const int total = take_chunk(x, pw, summask, list);
-        if (total == 0) break;
-        const uint32_t jv = (x.lane < total) ? list - 1u : x.nrows + x.nclusters;  // padding: the all-zero row
-        const uint32_t offv = __umul24(jv, x.rowbytes);
-        for (int i0 = 0; i0 < total; i0 += 4) {
-            uint32_t r[4][NW];
+        for (int t = 0; t < NW; ++t) {
+            pw[t] = v[t];
+            summask[t] = 0;
+        }
+        for (;;) {
+            uint32_t list;
+            const int total = take_chunk(x, pw, summask, list);
+            if (total == 0) break;
+            const uint32_t jv = (x.lane < total) ? list - 1u : x.nrows + x.nclusters;  // padding: the all-zero row
+            const uint32_t offv = __umul24(jv, x.rowbytes);
+            for (int i0 = 0; i0 < total; i0 += 4) {
+                uint32_t r[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+                for (int q = 0; q < 4; ++q)
+                    r[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, x.woffb[u], readlane(offv, i0 + q), 0);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int u = 0; u < NW; ++u) {
-                    uint32_t carry = r[q][u];
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t carry = r[q];
 #pragma unroll
                     for (int p = 0; p < D; ++p) {
-                        const uint32_t c2 = pl[p][u] & carry;
-                        pl[p][u] ^= carry;
+                        const uint32_t c2 = pl[p] & carry;
+                        pl[p] ^= carry;
                         carry = c2;
                     }
-                    ovf[u] |= carry;
+                    ovf |= carry;
                 }
+            }
         }
-    }
+        uint32_t e = ~ovf;
 #pragma unroll
-    for (int u = 0; u < NW; ++u) {
-        uint32_t e = ~ovf[u];
-#pragma unroll
-        for (int p = 0; p < D; ++p) e &= ((target >> p) & 1) ? pl[p][u] : ~pl[p][u];
+        for (int p = 0; p < D; ++p) e &= ((target >> p) & 1) ? pl[p] : ~pl[p];
         eq[u] = e;
     }
 }
@@ -562,7 +559,7 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
 // Register budget: 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per lane (2 for sum-of-sum at 4).
 template <int NW, int RULE, int LG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : RULE == GBNN_SUM_OF_MAX ? 5 : 4))) void
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : RULE == GBNN_SUM_OF_SUM ? 4 : 5))) void
 k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
