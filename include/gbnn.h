@@ -22,7 +22,7 @@
  *     Section IV-B "Batch Retrieval"); each byte must be 0 or 1 (any other value gives an
  *     unspecified, memory-safe result).
  *   - Limits: 2 <= C <= GBNN_MAX_C, L >= 1, n <= GBNN_MAX_N, 0 <= gamma <= GBNN_MAX_GAMMA,
- *     max_iters >= 1, K >= 0, M >= 0.
+ *     max_iters >= 1, 0 <= K <= GBNN_MAX_K, M >= 0.
  */
 #ifndef GBNN_H
 #define GBNN_H
@@ -37,6 +37,7 @@ extern "C" {
 #define GBNN_MAX_C 64
 #define GBNN_MAX_N 16384
 #define GBNN_MAX_GAMMA 32767
+#define GBNN_MAX_K 2147483647 /* probes per call */
 
 /* Retrieval rules. */
 typedef enum {

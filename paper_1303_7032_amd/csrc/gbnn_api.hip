@@ -80,7 +80,7 @@ size_t gbnn_w_bytes(int C, int L)
 
 size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule)
 {
-    if (!shape_ok(C, L) || K < 0 || !rule_ok(rule)) return 0;
+    if (!shape_ok(C, L) || K < 0 || K > GBNN_MAX_K || !rule_ok(rule)) return 0;
     return workspace_total_bytes(C, L, (int)gbnn_w_row_words(C, L));
 }
 
@@ -112,7 +112,7 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
                   void *stream)
 {
-    if (!shape_ok(C, L) || K < 0) return GBNN_ERR_SHAPE;
+    if (!shape_ok(C, L) || K < 0 || K > GBNN_MAX_K) return GBNN_ERR_SHAPE;
     if (!rule_ok(rule)) return GBNN_ERR_RULE;
     if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
     if (max_iters < 1) return GBNN_ERR_ITERS;
@@ -127,7 +127,7 @@ int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes
                           int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out,
                           void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!shape_ok(C, L) || K < 0) return GBNN_ERR_SHAPE;
+    if (!shape_ok(C, L) || K < 0 || K > GBNN_MAX_K) return GBNN_ERR_SHAPE;
     if (!rule_ok(rule)) return GBNN_ERR_RULE;
     if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
     if (max_iters < 1) return GBNN_ERR_ITERS;
@@ -144,7 +144,7 @@ const char *gbnn_strerror(int code)
     switch (code) {
     case GBNN_OK: return "ok";
     case GBNN_ERR_NULL: return "a required pointer is NULL";
-    case GBNN_ERR_SHAPE: return "shape outside the limits (2 <= C <= 64, L >= 1, C*L <= 16384, K >= 0, M >= 0)";
+    case GBNN_ERR_SHAPE: return "shape outside the limits (2 <= C <= 64, L >= 1, C*L <= 16384, 0 <= K < 2^31, M >= 0)";
     case GBNN_ERR_RULE: return "unknown retrieval rule";
     case GBNN_ERR_GAMMA: return "gamma outside [0, 32767]";
     case GBNN_ERR_ITERS: return "max_iters must be at least 1";

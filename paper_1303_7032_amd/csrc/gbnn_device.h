@@ -61,6 +61,10 @@ __device__ __forceinline__ uint32_t group_or(uint32_t v)
     return v;
 }
 
+// k * m for a probe index (below 2^31 by the interface limit) and a small positive m: one 32 x 32 -> 64
+// multiply instead of a 64 x 64 one.
+__device__ __forceinline__ int64_t probe_offset(int64_t k, int m) { return (int64_t)((uint64_t)(uint32_t)k * (uint32_t)m); }
+
 // Sum over the 2^LG lanes of this lane's group, left in every lane of the group (same butterfly).
 template <int CTRL>
 __device__ __forceinline__ uint32_t add_dpp(uint32_t v)

@@ -478,14 +478,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     x.bit0 = x.gl * 32u;
 
     // ---- probe load: 32 bytes per lane, packed to bits; or one symbol per cluster
-    const int64_t kmine = k0 + ((pvalid && upper) ? 1 : 0);
+    const int second = (pvalid && upper) ? 1 : 0;  // this lane's probe is k0 + second
+    const int64_t kmine = k0 + second;
     const uint32_t boff = (upper ? (uint32_t)a.n : 0u) + x.woffb * 8u;  // this lane's bytes, from the first probe of the pair
     constexpr uint32_t kInCluster = (1u << LGL) - 1u;
     uint32_t v;
     if (a.sym_in) {
-        v = x.valid ? symbol_word(a.sym_in[kmine * a.C + x.myc], (uint32_t)a.L, x.gl & kInCluster) : 0u;
+        const int32_t *sym = a.sym_in + probe_offset(k0, a.C) + second * a.C;
+        v = x.valid ? symbol_word(sym[x.myc], (uint32_t)a.L, x.gl & kInCluster) : 0u;
     } else {
-        const uint4 *p = reinterpret_cast<const uint4 *>(a.V0 + k0 * a.n + (x.valid ? boff : 0u));
+        const uint4 *p = reinterpret_cast<const uint4 *>(a.V0 + probe_offset(k0, a.n) + (x.valid ? boff : 0u));
         const uint4 lo = p[0], hi = p[1];
         v = x.valid ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
     }
@@ -640,13 +642,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     // ---- result store
     if (a.iters && x.gl == 0u && pvalid) a.iters[kmine] = upper ? it1 : it0;
     if (a.sym_in) {
-        if (a.bits_out && x.valid) a.bits_out[kmine * a.nw + x.gl] = v;
+        if (a.bits_out && x.valid) a.bits_out[probe_offset(k0, a.nw) + second * a.nw + x.gl] = v;
         if (a.sym_out) {
             const int32_t sy = cluster_symbol<LGL>(v, x.gl & kInCluster);
-            if (x.islead) a.sym_out[kmine * a.C + x.myc] = sy;
+            if (x.islead) a.sym_out[probe_offset(k0, a.C) + second * a.C + x.myc] = sy;
         }
     } else if (x.valid) {
-        uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + k0 * a.n + boff);
+        uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + probe_offset(k0, a.n) + boff);
         dst[0] = spread16(v & 0xFFFFu);
         dst[1] = spread16(v >> 16);
     }

@@ -590,12 +590,12 @@ k_retrieve_wave(RetrieveArgs a)
         // ---- probe load: 32 bytes per word, packed to bits; or one symbol per cluster
         uint32_t v[NW];
         if (a.sym_in) {
-            const int32_t *sym = a.sym_in + k * a.C;
+            const int32_t *sym = a.sym_in + probe_offset(k, a.C);
 #pragma unroll
             for (int t = 0; t < NW; ++t)
                 v[t] = x.valid[t] ? symbol_word(sym[x.myc[t]], (uint32_t)a.L, (uint32_t)x.lane & (LW - 1)) : 0u;
         } else {
-            const uint8_t *src = a.V0 + k * a.n;
+            const uint8_t *src = a.V0 + probe_offset(k, a.n);
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
                 const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
@@ -794,17 +794,17 @@ k_retrieve_wave(RetrieveArgs a)
             if (a.bits_out) {
 #pragma unroll
                 for (int t = 0; t < NW; ++t)
-                    if (x.valid[t]) a.bits_out[k * a.nw + t * 64 + x.lane] = v[t];
+                    if (x.valid[t]) a.bits_out[probe_offset(k, a.nw) + t * 64 + x.lane] = v[t];
             }
             if (a.sym_out) {
 #pragma unroll
                 for (int t = 0; t < NW; ++t) {
                     const int32_t sy = cluster_symbol<LG>(v[t], (uint32_t)x.lane & (LW - 1));
-                    if (x.islead[t]) a.sym_out[k * a.C + x.myc[t]] = sy;
+                    if (x.islead[t]) a.sym_out[probe_offset(k, a.C) + x.myc[t]] = sy;
                 }
             }
         } else {
-            uint8_t *dstb = a.Vout + k * a.n;
+            uint8_t *dstb = a.Vout + probe_offset(k, a.n);
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
                 if (x.valid[t]) {

@@ -55,7 +55,7 @@ def test_retrieve_argument_errors(lib):
         return lib.gbnn_retrieve(W, C, L, V0, Vout, K, rule, gamma, cap, it, wsp, wsb, 0)
 
     assert call(C=1) == E["SHAPE"] and call(C=65, L=1) == E["SHAPE"] and call(L=0) == E["SHAPE"]
-    assert call(C=64, L=257) == E["SHAPE"] and call(K=-1) == E["SHAPE"]
+    assert call(C=64, L=257) == E["SHAPE"] and call(K=-1) == E["SHAPE"] and call(K=2 ** 31) == E["SHAPE"]
     assert call(rule=3) == E["RULE"] and call(rule=-1) == E["RULE"]
     assert call(gamma=-1) == E["GAMMA"] and call(gamma=32768) == E["GAMMA"]
     assert call(cap=0) == E["ITERS"]
