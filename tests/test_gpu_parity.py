@@ -244,7 +244,7 @@ def test_messages_at_the_boundary_edge_cases(networks):
 
 
 @pytest.mark.parametrize("C,L,M", [(4, 16, 50), (5, 12, 200), (8, 32, 300), (8, 128, 5000), (8, 256, 20000),
-                                    (16, 512, 100000), (32, 32, 700), (2, 512, 30000)])
+                                    (16, 512, 100000), (32, 32, 700), (2, 512, 30000), (12, 256, 20000)])
 @pytest.mark.parametrize("rule", RULES)
 def test_arbitrary_binary_probes(networks, C, L, M, rule):
     """Probes outside the one-active-neuron-per-cluster contract: several active neurons in a
@@ -313,6 +313,26 @@ def test_later_passes_many_caps_and_dying_clusters(networks, M, rule):
             erased_part_dead = (ref.reshape(len(ref), C, L).sum(axis=2) == 0).any(axis=1)
             seen_dead_late += int((erased_part_dead & (itref >= 3)).sum())
     assert seen_capped > 0 and seen_dead_late > 0, "the sample must hold capped probes and probes that lose a cluster late"
+
+
+@pytest.mark.parametrize("C,L,M,K", [(8, 128, 9000, 20000), (8, 256, 30000, 20000), (12, 256, 45000, 6000)])
+@pytest.mark.parametrize("rule", ["sum_of_max", "hybrid"])
+def test_many_probes_around_the_candidate_limit(networks, C, L, M, K, rule):
+    """Networks dense enough that the number of candidates left by pass 1 straddles the limit of the
+    candidate-matrix passes (28 per probe with two probes per wave, 32 with one), so that probes
+    just below and just above it sit side by side, in both kernel families that serve the shape."""
+    msgs, Wo, Wd = networks(C, L, M)
+    e = C // 2
+    q, er = inputs.make_probe_plan(C, M, K, e, 77)
+    V0 = inputs.one_hot(msgs[q], L, er)
+    ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, 1, 20)
+    # candidates after pass 1 = what the hybrid's first pass leaves in the erased clusters
+    first, _, _ = orc.retrieve(Wo, C, L, V0, "hybrid", 1, 1)
+    cands = (first.astype(np.int32).sum(axis=1) - (C - e))
+    assert (cands < 26).any() and (cands > 34).any(), f"candidates range {cands.min()}..{cands.max()}"
+    for nm, kw in [("default", {})] + [a for a in other_paths(C, L, rule) if a[0] != "generic"]:
+        out, it = dev_retrieve(Wd, C, L, V0, rule, 1, 20, **kw)
+        check_same(out, it, ref, itref, f"{rule} {nm}")
 
 
 def test_edge_cases(networks):
