@@ -20,11 +20,16 @@
 //     AND of the known neurons' rows when each known cluster holds one active neuron, the counter
 //     form otherwise; later passes are the sum-of-max update applied to erased clusters only.
 //
-// The kernel is bound by instruction issue (scalar and vector instructions cost alike), not by
-// memory latency, so everything per pass is kept to a few vector instructions: cluster-wide flags
-// are DPP butterflies over the lanes of a group, the listing of active neurons ranks set bits with
-// ballot + mbcnt and pushes their indices to lane `rank` with ds_permute, and the row loop is one
-// v_readlane plus one buffer_load (row offset in the scalar-offset operand) per row.
+// The usual probe (one active neuron per known cluster, a few candidates left in the erased clusters
+// by pass 1) leaves the vector form after pass 1: the later passes run on the candidates' adjacency
+// matrix, one candidate per lane (candidate_passes).  Crowded clusters (dense networks) are walked
+// lane by lane without a list (apply_by_cluster).
+//
+// The kernel is bound by instruction issue (scalar and vector instructions cost alike) on top of
+// the probe and result traffic, so everything per pass is kept to a few vector instructions:
+// cluster-wide flags are DPP butterflies over the lanes of a group, the listing of active neurons
+// ranks set bits with ballot + mbcnt and pushes their indices to lane `rank` with ds_permute, and
+// the row loop is one v_readlane plus one buffer_load (row offset in the scalar-offset operand) per row.
 
 #include "gbnn_device.h"
 #include "gbnn_internal.h"
