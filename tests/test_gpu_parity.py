@@ -370,6 +370,30 @@ def test_edge_cases(networks):
     assert int(raw[:3].sum()) == 0 and int(raw[3 + V0.size:].sum()) == 0
 
 
+def test_streams_share_a_workspace(networks):
+    """Calls enqueue on the caller's stream and only read the prepared workspace, so two streams may run
+    retrievals on the same network at the same time."""
+    C, L, M = 8, 256, 20000
+    msgs, Wo, Wd = networks(C, L, M)
+    ws = gb.gbnn_prepare(Wd, C, L)
+    torch.cuda.synchronize()
+    jobs = []
+    for i, rule in enumerate(("sum_of_max", "hybrid", "sum_of_sum", "sum_of_max")):
+        q, er = inputs.make_probe_plan(C, M, 3000 + i, 4, 50 + i)
+        V0 = inputs.one_hot(msgs[q], L, er)
+        jobs.append((rule, V0, torch.from_numpy(V0).cuda(), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    results = []
+    for _ in range(3):                      # several rounds in flight on every stream
+        for rule, V0, V0d, st in jobs:
+            with torch.cuda.stream(st):
+                results.append((rule, V0, gb.gbnn_retrieve(Wd, C, L, V0d, rule, 1, 20, workspace=ws)))
+    torch.cuda.synchronize()
+    for rule, V0, (out, it) in results:
+        ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, 1, 20)
+        check_same(out.cpu().numpy(), it.cpu().numpy(), ref, itref, f"{rule} on its own stream")
+
+
 def test_argument_errors_reach_python():
     W = gb.new_network(4, 16)
     V = torch.zeros((2, 64), dtype=torch.uint8, device="cuda")
