@@ -116,6 +116,13 @@ def test_oscillation_example_through_the_abi():
     assert (out[0] == vec["v1"]).all() and it[0] == 1
     out, it = dev_retrieve(W, C, L, vec["v0"][None, :].copy(), "hybrid", 1, 20)
     assert (out[0] == vec["v1"]).all() and it[0] == 2
+    # the same through the message boundary: probe "erased, erased, 1" as symbols
+    probe = np.array([[int(x) - 1 for x in g["probe_1based"][0].split()]], dtype=np.int32)
+    for cap, want in {1: "v1", 2: "v2", 3: "v3"}.items():
+        bits, sym, it = dev_retrieve_symbols(W, C, L, probe, "sum_of_sum", 1, cap)
+        assert int(bits.view(np.uint32)[0, 0]) == sum(int(b) << i for i, b in enumerate(vec[want])) and it[0] == -cap
+        _, rsym = orc.decode(C, L, vec[want][None, :])
+        assert (sym == rsym).all()
 
 
 # ------------------------------------------------------------------------------- small / medium shapes

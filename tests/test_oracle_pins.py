@@ -447,3 +447,24 @@ def test_retrieve_symbols_is_retrieve_on_the_one_hot_probe():
                 cnt = int(act[c].sum())
                 assert sym[k, c] == (int(act[c].argmax()) if cnt == 1 else (-1 if cnt == 0 else -2))
             assert [(int(bits[k, i // 32]) >> (i % 32)) & 1 for i in range(C * L)] == ref[k].tolist()
+
+
+def test_worked_example_through_the_message_boundary():
+    """Section V-A with the probe given as symbols ("erased, erased, 1"): the packed results and symbols
+    after 1, 2, 3 passes must be the decodings of the printed v^1, v^2, v^3."""
+    g = read_golden("oscillation_example.txt")
+    C, L = int(g["C"][0]), int(g["L"][0])
+    msgs = np.array([[int(x) - 1 for x in m.split()] for m in g["messages_1based"][0].split("/")], dtype=np.int32)
+    probe = np.array([[int(x) - 1 for x in g["probe_1based"][0].split()]], dtype=np.int32)   # 0 -> -1 = erased
+    W, _ = orc.store(C, L, msgs)
+    assert orc.encode_probes(C, L, probe)[0].tolist() == [int(x) for x in g["v0"][0].split()]
+    for cap, key in ((1, "v1"), (2, "v2"), (3, "v3")):
+        v = [int(x) for x in g[key][0].split()]
+        bits, sym, it = orc.retrieve_symbols(W, C, L, probe, "sum_of_sum", 1, cap)
+        assert it[0] == -cap
+        assert int(bits[0, 0]) == sum(b << i for i, b in enumerate(v))
+        want = []
+        for c in range(C):
+            on = [l for l in range(L) if v[c * L + l]]
+            want.append(on[0] if len(on) == 1 else (-1 if not on else -2))
+        assert sym[0].tolist() == want
