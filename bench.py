@@ -73,6 +73,21 @@ def main() -> int:
     torch.cuda.synchronize()
     store_s = time.perf_counter() - t0
 
+    # the same store into a zeroed scratch network, bracketed by events (device time, first call excluded)
+    W2 = gb.new_network(C, L)
+    store_us = []
+    for _ in range(5):
+        W2.zero_()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        gb.gbnn_store(W2, C, L, msgs_d)
+        ev1.record()
+        torch.cuda.synchronize()
+        store_us.append(ev0.elapsed_time(ev1) * 1e3)
+    assert torch.equal(W, W2)
+    del W2
+    store_event_us = sorted(store_us)[len(store_us) // 2]
+
     outs = {r: torch.empty_like(V0d) for r in rules}
     iters = {r: torch.empty(K, dtype=torch.int32, device="cuda") for r in rules}
     ws = torch.empty(gb.gbnn_workspace_bytes(C, L, K, rules[0]), dtype=torch.uint8, device="cuda")
@@ -237,7 +252,8 @@ def main() -> int:
         "cpu_baseline": cpu,
         "per_rule": per_rule,
         "message_boundary": message_boundary,
-        "store": {"messages": w.M, "seconds_incl_launch_and_sync": store_s,
+        "store": {"messages": w.M, "seconds_incl_launch_and_sync": store_s, "event_us": store_event_us,
+                  "messages_per_second": w.M / (store_event_us * 1e-6),
                   "prepare_seconds_incl_launch_and_sync": prepare_s},
     }
     print(json.dumps(line))

@@ -75,6 +75,8 @@ size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule);
  *   msgs   device, int32_t[M][C], 0-based symbols
  *   status device int32_t or NULL; bit 0 is OR-ed in if some message had a symbol outside
  *          [0,L); such a message is skipped entirely.  Zero it before the call.
+ * Calls that store into the same W must not overlap in time (order them on one stream): rows of W
+ * are updated with plain loads and stores.
  */
 int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream);
 

@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/gbnn.h: argument checks and kernel dispatch.
 #include <cstdlib>
+#include <cstring>
 
 #include "gbnn_internal.h"
 
@@ -88,8 +89,13 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
 {
     if (!shape_ok(C, L) || M < 0) return GBNN_ERR_SHAPE;
     if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
-    const hipError_t e =
-        launch_store(W, C, L, (int)gbnn_w_row_words(C, L), msgs, M, status, static_cast<hipStream_t>(stream));
+    int path = kStoreAuto;  // GBNN_STORE_PATH=atomic|rows forces one of the two kernels (tests)
+    if (const char *p = std::getenv("GBNN_STORE_PATH")) {
+        if (std::strcmp(p, "atomic") == 0) path = kStoreAtomic;
+        if (std::strcmp(p, "rows") == 0) path = kStoreRows;
+    }
+    const hipError_t e = launch_store(W, C, L, (int)gbnn_w_row_words(C, L), msgs, M, status, path,
+                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 

@@ -45,8 +45,12 @@ inline size_t workspace_total_bytes(int C, int L, int nw) { return workspace_ful
 int wave_words_per_lane(int C, int L);
 bool half_wave_serves(int C, int L);
 
+// Which storing kernel: chosen by the number of messages, or forced (tests).
+enum { kStoreAuto = 0, kStoreAtomic = 1, kStoreRows = 2 };
+constexpr int64_t kStoreRowsMinMessages = 64;
+constexpr int kStoreBlocks = 256;
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
-                        hipStream_t s);
+                        int path, hipStream_t s);
 hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
                           hipStream_t s);
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);

@@ -1,4 +1,5 @@
 // Storing messages as cliques (Section II-A) and the per-cluster summary rows of W.
+#include "gbnn_device.h"
 #include "gbnn_internal.h"
 
 namespace gbnn {
@@ -34,6 +35,109 @@ __global__ __launch_bounds__(256) void k_store(uint32_t *W, int C, int L, int nw
             uint32_t *p = row + (col >> 5);
             // A stale read can only cause a redundant OR, never a missed one.
             if (!(*p & bit)) atomicOr(p, bit);
+        }
+    }
+}
+
+// The same result for many messages, without global atomics.  A workgroup owns the rows of R
+// consecutive neurons of one cluster c and builds them in LDS, then ORs the non-zero words into W with
+// plain loads and stores -- no other workgroup of the launch touches those rows.  Every wave scans its
+// share of the symbol column of cluster c and queues the messages whose symbol falls among the
+// workgroup's neurons; whenever 64 or more are queued, the wave walks the queued messages with one lane
+// per (message, cluster) pair -- consecutive lanes read consecutive symbols -- and sets the pair's bit
+// with an LDS atomic.  A message with a symbol outside [0,L) is skipped by every workgroup that meets it
+// and reported by the first workgroup of the cluster the bad symbol is in.
+constexpr int kStoreThreads = 1024;
+constexpr int kStoreWaves = kStoreThreads / 64;
+constexpr int kStoreUnroll = 8;   // symbol loads in flight per lane: the scan is a chain of round trips otherwise
+constexpr int kStoreQueue = 128;  // per wave: fewer than 64 left over plus at most 64 new ones
+constexpr int kStoreLdsBytes = 64 * 1024 - kStoreWaves * kStoreQueue * 4;  // what is left for the rows
+
+// kPow2: C is a power of two (it then divides 64, and a message's C pairs sit in one wave instruction, so
+// its validity is one ballot); otherwise the lane that queues a message checks all of its symbols first.
+template <bool kPow2>
+__global__ __launch_bounds__(kStoreThreads) void k_store_rows(uint32_t *W, int C, int L, int nw, int R,
+                                                              int blocks_per_cluster,
+                                                              const int32_t *__restrict__ msgs, int64_t M,
+                                                              int32_t *__restrict__ status)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t *rows = lds;  // [R][nw]
+    const int lane = threadIdx.x & 63;
+    uint32_t *queue = lds + R * nw + (threadIdx.x >> 6) * kStoreQueue;
+    const int c = blockIdx.x / blocks_per_cluster;
+    const int b = blockIdx.x - c * blocks_per_cluster;
+    const int l0 = b * R;
+    const int l1 = l0 + R < L ? l0 + R : L;
+    const int words = (l1 - l0) * nw;
+    const int lgC = __builtin_ctz((unsigned)C);  // used when kPow2
+    for (int t = threadIdx.x; t < words; t += kStoreThreads) rows[t] = 0u;
+    __syncthreads();
+
+    int cnt = 0;  // queued messages of this wave (the same in every lane)
+    auto flush = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int pairs = cnt * C;
+        for (int p0 = 0; p0 < pairs; p0 += 64) {
+            const int p = p0 + lane;
+            const bool in = p < pairs;
+            const int q = !in ? 0 : kPow2 ? p >> lgC : p / C;
+            const int c2 = p - q * C;
+            const int32_t *sym = msgs + (int64_t)queue[q] * C;
+            const int32_t s2 = in ? sym[c2] : 0;
+            const int32_t sc = sym[c];  // within [l0, l1): checked when queued
+            bool ok = in;
+            if (kPow2) {
+                const uint64_t bad_lanes = ballot(in && (uint32_t)s2 >= (uint32_t)L);
+                const uint64_t mine = C == 64 ? ~0ull : ((1ull << C) - 1ull) << (lane - c2);
+                ok = ok && (bad_lanes & mine) == 0;
+            }
+            if (ok && c2 != c) {
+                const int col = c2 * L + s2;
+                atomicOr(rows + (sc - l0) * nw + (col >> 5), 1u << (col & 31));
+            }
+        }
+        cnt = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    bool bad = false;
+    for (int64_t base = 0; base < M; base += (int64_t)kStoreThreads * kStoreUnroll) {
+        int32_t s[kStoreUnroll];
+#pragma unroll
+        for (int u = 0; u < kStoreUnroll; ++u) {
+            const int64_t m = base + u * kStoreThreads + threadIdx.x;
+            s[u] = m < M ? msgs[m * C + c] : l1;  // l1: outside this block, yet not a bad symbol
+        }
+#pragma unroll
+        for (int u = 0; u < kStoreUnroll; ++u) {
+            const int64_t m = base + u * kStoreThreads + threadIdx.x;
+            if (m < M && (uint32_t)s[u] >= (uint32_t)L) bad = bad || b == 0;
+            bool match = m < M && s[u] >= l0 && s[u] < l1;
+            if (!kPow2 && match) {
+                const int32_t *sym = msgs + m * C;
+                for (int c2 = 0; c2 < C; ++c2) match = match && (uint32_t)sym[c2] < (uint32_t)L;
+            }
+            const uint64_t takers = ballot(match);
+            if (takers) {
+                if (match) queue[cnt + (int)mbcnt(takers)] = (uint32_t)m;
+                cnt += __builtin_popcountll(takers);
+                if (cnt >= 64) flush();
+            }
+        }
+    }
+    if (cnt) flush();
+    if (bad && status) atomicOr(status, 1);
+    __syncthreads();
+    uint32_t *out = W + ((int64_t)c * L + l0) * nw;
+    for (int t = threadIdx.x; t < words; t += kStoreThreads) {
+        const uint32_t v = rows[t];
+        if (v) {
+            const uint32_t old = out[t];
+            if (v & ~old) out[t] = old | v;
         }
     }
 }
@@ -76,23 +180,30 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
 }
 
 // full = bit c set iff the summary row of cluster c has every neuron's bit: then every neuron has a
-// neighbour in c (or is in c), and a fully active cluster c switches nobody off.  One wave; lane c checks
-// row c.  With the densities the method works at this is the rule, and retrieval skips those rows.
-__global__ __launch_bounds__(64) void k_summary_full(const uint32_t *__restrict__ has, int C, int n, int nw,
-                                                     uint64_t *__restrict__ full)
+// neighbour in c (or is in c), and a fully active cluster c switches nobody off.  With the densities the
+// method works at this is the rule, and retrieval skips those rows.  One workgroup of 16 waves; a wave
+// checks the rows of clusters wave, wave + 16, ..., its lanes striding over the words.
+__global__ __launch_bounds__(1024) void k_summary_full(const uint32_t *__restrict__ has, int C, int n, int nw,
+                                                       uint64_t *__restrict__ full)
 {
-    const int c = threadIdx.x;
-    bool all = c < C;
-    if (c < C) {
+    __shared__ uint32_t row_full[GBNN_MAX_C];
+    const int lane = threadIdx.x & 63;
+    for (int c = threadIdx.x >> 6; c < C; c += 16) {
         const uint32_t *row = has + (int64_t)c * nw;
-        for (int w = 0; w < nw; ++w) {
+        bool all = true;
+        for (int w = lane; w < nw; w += 64) {
             const int bits = n - 32 * w;  // neurons in this word
             const uint32_t need = bits >= 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
             all = all && (row[w] & need) == need;
         }
+        const bool every = ballot(!all) == 0;
+        if (lane == 0) row_full[c] = every ? 1u : 0u;
     }
-    const uint64_t m = __ballot(all);
-    if (c == 0) *full = m;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const uint64_t m = ballot(lane < C && row_full[lane < C ? lane : 0] != 0u);
+        if (lane == 0) *full = m;
+    }
 }
 
 // Wb = W with the intra-cluster blocks set to all ones: row j gets the bits of j's own cluster.
@@ -115,9 +226,30 @@ __global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict_
 }  // namespace
 
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
-                        hipStream_t s)
+                        int path, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
+    // A handful of messages: one atomic OR per bit.  More: rows built in LDS, provided a block of rows
+    // fits (it always does within the shape limits of the interface).
+    const int rmax = kStoreLdsBytes / (nw * 4);
+    const bool rows = path == kStoreRows || (path == kStoreAuto && M >= kStoreRowsMinMessages);
+    if (rows && rmax >= 1 && M <= 0x7FFFFFFF) {  // (queued message numbers are 32-bit)
+        // About kStoreBlocks workgroups (one per compute unit): each scans the symbol column of its cluster
+        // for all M messages, so fewer, larger ones scan less and more of them share the pair work.
+        int R = (C * L + kStoreBlocks - 1) / kStoreBlocks;
+        if (R > rmax) R = rmax;
+        if (R > L) R = L;
+        if (R < 1) R = 1;
+        const int bpc = (L + R - 1) / R;
+        const size_t lds = (size_t)R * nw * 4 + kStoreWaves * kStoreQueue * 4;
+        if ((C & (C - 1)) == 0)
+            hipLaunchKernelGGL(k_store_rows<true>, dim3((unsigned)(C * bpc)), dim3(kStoreThreads), lds, s, W, C, L, nw,
+                               R, bpc, msgs, M, status);
+        else
+            hipLaunchKernelGGL(k_store_rows<false>, dim3((unsigned)(C * bpc)), dim3(kStoreThreads), lds, s, W, C, L,
+                               nw, R, bpc, msgs, M, status);
+        return hipGetLastError();
+    }
     const int64_t total = M * C;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
@@ -132,7 +264,7 @@ hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has
     hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(64), 0, s, has, C, C * L, nw, full);
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, C * L, nw, full);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t words = (int64_t)C * L * nw;

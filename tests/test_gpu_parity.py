@@ -25,6 +25,14 @@ def _need_gpu():
     gb.lib()  # fails loudly if the HIP library is not built
 
 
+@pytest.fixture(params=["auto", "atomic", "rows"])
+def store_path(request, monkeypatch):
+    """Both storing kernels (one atomic OR per bit; rows built in LDS), and the library's own choice."""
+    if request.param != "auto":
+        monkeypatch.setenv("GBNN_STORE_PATH", request.param)
+    return request.param
+
+
 def dev_store(C, L, msgs):
     W = gb.new_network(C, L)
     status = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -71,7 +79,7 @@ def check_same(out, it, ref, itref, what):
 
 # ------------------------------------------------------------------------------- storing
 @pytest.mark.parametrize("name", list(inputs.WORKLOADS))
-def test_store_bit_exact(name):
+def test_store_bit_exact(name, store_path):
     w = inputs.WORKLOADS[name]
     msgs = w.messages()
     Wd, st = dev_store(w.C, w.L, msgs)
@@ -81,8 +89,9 @@ def test_store_bit_exact(name):
     assert (got == orc.pack_bits(Wo)).all()
 
 
-@pytest.mark.parametrize("C,L,M", [(3, 3, 4), (5, 12, 200), (7, 33, 500), (2, 1, 3), (64, 256, 3000)])
-def test_store_odd_shapes_incremental_and_status(C, L, M):
+@pytest.mark.parametrize("C,L,M", [(3, 3, 4), (5, 12, 200), (7, 33, 500), (2, 1, 3), (64, 256, 3000), (6, 700, 9000),
+                                   (4, 2048, 30000), (16, 1024, 2000)])
+def test_store_odd_shapes_incremental_and_status(C, L, M, store_path):
     msgs = inputs.make_messages(C, L, M, 17)
     Wo, _ = orc.store(C, L, msgs)
     # two calls, second one overlapping the first, plus messages with bad symbols
@@ -92,7 +101,7 @@ def test_store_odd_shapes_incremental_and_status(C, L, M):
     W = gb.new_network(C, L)
     status = torch.zeros(1, dtype=torch.int32, device="cuda")
     h = M // 2
-    for part in (msgs[:h], msgs[h // 2:], bad[:2]):
+    for part in (msgs[:h], np.concatenate([msgs[h // 2:h], bad[:1], msgs[h:], bad[1:2]]), bad[:2]):
         gb.gbnn_store(W, C, L, torch.from_numpy(np.ascontiguousarray(part)).cuda(), status)
     assert int(status.item()) == 1
     assert (W.cpu().numpy().view(np.uint32) == orc.pack_bits(Wo)).all()
