@@ -95,6 +95,19 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
 int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Storing a few more messages (Section II-A) into W and into a workspace that gbnn_prepare has
+ * filled for W as it was: afterwards W and the workspace are what gbnn_store followed by
+ * gbnn_prepare would have produced, without the pass over all of W.  Meant for storing and
+ * retrieving in turn, one message or a handful at a time (the one-after-another use that
+ * Section VII-C sets against batches); its cost grows with M, one atomic update per bit.
+ *   W, msgs, M, status   as for gbnn_store
+ *   workspace  device, as for gbnn_prepare; read and written.  Retrievals that read it must not
+ *          overlap this call in time.
+ */
+int gbnn_store_update(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
  * Retrieval of K probes, each independently, iterated until its activity vector is reproduced
  * by a pass or max_iters passes have been made.
  *   V0     device, uint8_t[K][n]; an erased cluster is all-zero for EVERY rule, the library

@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_store.argtypes = [vp, ci, ci, vp, i64, vp, vp]
         L.gbnn_prepare.restype = ci
         L.gbnn_prepare.argtypes = [vp, ci, ci, vp, sz, vp]
+        L.gbnn_store_update.restype = ci
+        L.gbnn_store_update.argtypes = [vp, ci, ci, vp, i64, vp, vp, sz, vp]
         L.gbnn_retrieve.restype = ci
         L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
         L.gbnn_retrieve_symbols.restype = ci
@@ -113,6 +115,23 @@ def gbnn_store(W: torch.Tensor, C: int, L: int, msgs: torch.Tensor, status: torc
         st = status.data_ptr()
     M = msgs.numel() // C
     _check(lib().gbnn_store(W.data_ptr(), C, L, msgs.data_ptr() if M else 0, M, st, _stream(W)))
+
+
+def gbnn_store_update(W: torch.Tensor, C: int, L: int, msgs: torch.Tensor, workspace: torch.Tensor,
+                      status: torch.Tensor | None = None) -> None:
+    """gbnn_store into W and into the workspace prepared for it, so that retrieval can follow at once."""
+    _dev(W, torch.int32, "W")
+    _dev(msgs, torch.int32, "msgs")
+    _dev(workspace, torch.uint8, "workspace")
+    if W.numel() * 4 != gbnn_w_bytes(C, L) or msgs.numel() % C:
+        _check(ERRORS["SHAPE"])
+    st = 0
+    if status is not None:
+        _dev(status, torch.int32, "status")
+        st = status.data_ptr()
+    M = msgs.numel() // C
+    _check(lib().gbnn_store_update(W.data_ptr(), C, L, msgs.data_ptr() if M else 0, M, st, workspace.data_ptr(),
+                                   workspace.numel(), _stream(W)))
 
 
 def gbnn_prepare(W: torch.Tensor, C: int, L: int, workspace: torch.Tensor | None = None) -> torch.Tensor:

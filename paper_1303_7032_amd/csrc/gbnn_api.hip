@@ -114,6 +114,22 @@ int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t worksp
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
+int gbnn_store_update(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    if (!shape_ok(C, L) || M < 0) return GBNN_ERR_SHAPE;
+    if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
+    const int nw = (int)gbnn_w_row_words(C, L);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, nw))
+        return GBNN_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    const hipError_t e = launch_store_update(
+        W, C, L, nw, msgs, M, status, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
+        reinterpret_cast<uint32_t *>(ws), reinterpret_cast<uint64_t *>(ws + workspace_full_offset(C, L, nw)),
+        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
 int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
                   void *stream)

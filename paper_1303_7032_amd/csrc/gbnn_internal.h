@@ -51,6 +51,8 @@ constexpr int64_t kStoreRowsMinMessages = 64;
 constexpr int kStoreBlocks = 256;
 hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
                         int path, hipStream_t s);
+hipError_t launch_store_update(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
+                               uint32_t *has, uint32_t *Wb, uint64_t *full, hipStream_t s);
 hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
                           hipStream_t s);
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);

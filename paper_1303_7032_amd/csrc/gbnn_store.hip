@@ -39,6 +39,39 @@ __global__ __launch_bounds__(256) void k_store(uint32_t *W, int C, int L, int nw
     }
 }
 
+// Storing into W and into an already prepared table at once (a few messages between retrievals): the
+// thread of (message m, cluster c) sets, for the message's neuron a of cluster c and its neuron b of every
+// other cluster, bit b of row a in W and in the table's copy of W, and bit b of the summary row of cluster
+// c (b now has a neighbour in c).  The own-cluster blocks and own bits of the table stay as they are.
+__global__ __launch_bounds__(256) void k_store_update(uint32_t *W, uint32_t *Wb, uint32_t *has, int C, int L, int nw,
+                                                      const int32_t *__restrict__ msgs, int64_t M,
+                                                      int32_t *__restrict__ status)
+{
+    const int64_t total = M * C;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t m = t / C;
+        const int c = (int)(t - m * C);
+        const int32_t *sym = msgs + m * C;
+        bool ok = true;
+        for (int c2 = 0; c2 < C; ++c2) ok = ok && (uint32_t)sym[c2] < (uint32_t)L;
+        if (!ok) {
+            if (c == 0 && status) atomicOr(status, 1);
+            continue;
+        }
+        const int64_t row = ((int64_t)c * L + sym[c]) * nw;
+        for (int c2 = 0; c2 < C; ++c2) {
+            if (c2 == c) continue;
+            const int col = c2 * L + sym[c2];
+            const uint32_t bit = 1u << (col & 31);
+            const int w = col >> 5;
+            if (!(W[row + w] & bit)) atomicOr(W + row + w, bit);
+            if (!(Wb[row + w] & bit)) atomicOr(Wb + row + w, bit);
+            if (!(has[(int64_t)c * nw + w] & bit)) atomicOr(has + (int64_t)c * nw + w, bit);
+        }
+    }
+}
+
 // The same result for many messages, without global atomics.  A workgroup owns the rows of R
 // consecutive neurons of one cluster c and builds them in LDS, then ORs the non-zero words into W with
 // plain loads and stores -- no other workgroup of the launch touches those rows.  Every wave scans its
@@ -254,6 +287,20 @@ hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, 
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(k_store, dim3((unsigned)blocks), dim3(256), 0, s, W, C, L, nw, msgs, M, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_store_update(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
+                               uint32_t *has, uint32_t *Wb, uint64_t *full, hipStream_t s)
+{
+    if (M == 0) return hipSuccess;
+    const int64_t total = M * C;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_store_update, dim3((unsigned)blocks), dim3(256), 0, s, W, Wb, has, C, L, nw, msgs, M, status);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, C * L, nw, full);
     return hipGetLastError();
 }
 

@@ -99,6 +99,18 @@ def test_prepare_argument_errors(lib):
     assert lib.gbnn_prepare(0x1000, 8, 256, 0x10000, need - 1, 0) == E["WORKSPACE"]
 
 
+def test_store_update_argument_errors(lib):
+    E = gb.ERRORS
+    need = gb.gbnn_workspace_bytes(8, 256, 0, "hybrid")
+    assert lib.gbnn_store_update(0x1000, 1, 4, 0x1000, 1, 0, 0x10000, need, 0) == E["SHAPE"]
+    assert lib.gbnn_store_update(0x1000, 8, 256, 0x1000, -1, 0, 0x10000, need, 0) == E["SHAPE"]
+    assert lib.gbnn_store_update(0, 8, 256, 0x1000, 1, 0, 0x10000, need, 0) == E["NULL"]
+    assert lib.gbnn_store_update(0x1000, 8, 256, 0, 1, 0, 0x10000, need, 0) == E["NULL"]
+    assert lib.gbnn_store_update(0x1000, 8, 256, 0x1000, 1, 0, 0, need, 0) == E["WORKSPACE"]
+    assert lib.gbnn_store_update(0x1000, 8, 256, 0x1000, 1, 0, 0x10010, need, 0) == E["WORKSPACE"]
+    assert lib.gbnn_store_update(0x1000, 8, 256, 0x1000, 1, 0, 0x10000, need - 1, 0) == E["WORKSPACE"]
+
+
 def test_strerror_and_path(lib):
     for code in range(-8, 1):
         assert gb.gbnn_strerror(code)
