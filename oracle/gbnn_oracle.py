@@ -204,3 +204,35 @@ def retrieve_symbols(W, C, L, probes, rule, gamma=1, max_iters=20, nthreads=0):
     out, iters, _ = retrieve(W, C, L, encode_probes(C, L, probes), rule, gamma, max_iters, nthreads)
     bits, sym = decode(C, L, out)
     return bits, sym, iters
+
+
+# ------------------------------------------------------------------ sparse W' (Section IV-B, "Sparsification")
+def sparsify(W: np.ndarray):
+    """W -> W': only the nonzero elements and their coordinates, row by row.  Returns
+    (offsets int64[n+1], cols int64[nnz]): the neighbours of neuron i are cols[offsets[i]:offsets[i+1]],
+    in ascending order."""
+    n = W.shape[0]
+    offsets = np.zeros(n + 1, dtype=np.int64)
+    cols = []
+    for i in range(n):
+        nz = np.nonzero(W[i])[0]
+        cols.append(nz)
+        offsets[i + 1] = offsets[i] + len(nz)
+    return offsets, (np.concatenate(cols) if cols else np.zeros(0, dtype=np.int64)).astype(np.int64)
+
+
+def som_pass_lists(C: int, L: int, offsets: np.ndarray, cols: np.ndarray, v: np.ndarray) -> np.ndarray:
+    """One sum-of-max pass (Eq. 6-7 with gamma = 1) computed from W' alone: an active neuron stays on
+    iff each of the C-1 other clusters holds an active neuron of its neighbour list."""
+    n = C * L
+    out = np.zeros(n, dtype=np.uint8)
+    for i in range(n):
+        if not v[i]:
+            continue
+        seen = np.zeros(C, dtype=bool)
+        for j in cols[offsets[i]:offsets[i + 1]]:
+            if v[j]:
+                seen[j // L] = True
+        seen[i // L] = True
+        out[i] = 1 if seen.all() else 0
+    return out

@@ -468,3 +468,35 @@ def test_worked_example_through_the_message_boundary():
             on = [l for l in range(L) if v[c * L + l]]
             want.append(on[0] if len(on) == 1 else (-1 if not on else -2))
         assert sym[0].tolist() == want
+
+
+# ------------------------------------------------------------------ sparse W' (Section IV-B, "Sparsification")
+def test_sparsify_round_trip_and_degrees():
+    C, L, M = 5, 12, 60
+    W, _ = orc.store(C, L, inputs.make_messages(C, L, M, 9))
+    off, cols = orc.sparsify(W)
+    assert off[0] == 0 and off[-1] == len(cols) == int(W.sum())
+    back = np.zeros_like(W)
+    for i in range(C * L):
+        row = cols[off[i]:off[i + 1]]
+        assert (np.diff(row) > 0).all()                       # ascending, no repeats
+        assert (row // L != i // L).all()                     # no neighbour in the own cluster
+        back[i, row] = 1
+    assert (back == W).all()
+    # by hand: the clique of one message (2,0,1) in a 3 x 3 network
+    W1, _ = orc.store(3, 3, np.array([[2, 0, 1]], dtype=np.int32))
+    off1, cols1 = orc.sparsify(W1)
+    assert off1.tolist() == [0, 0, 0, 2, 4, 4, 4, 4, 6, 6] and cols1.tolist() == [3, 7, 2, 7, 2, 3]
+
+
+def test_sum_of_max_from_the_lists_is_sum_of_max_from_the_matrix():
+    """W' loses nothing: a pass computed from the neighbour lists equals Eq. (6)-(7) on W, on arbitrary states."""
+    rng = np.random.default_rng(12)
+    for (C, L, M) in [(4, 8, 30), (3, 5, 10), (6, 16, 300)]:
+        W, _ = orc.store(C, L, inputs.make_messages(C, L, M, 4))
+        off, cols = orc.sparsify(W)
+        for _ in range(25):
+            v = (rng.random(C * L) < rng.choice([0.1, 0.4, 0.9])).astype(np.uint8)
+            if rng.random() < 0.3:
+                v[: L] = 0                                     # an empty cluster: everything goes off
+            assert (orc.som_pass_lists(C, L, off, cols, v) == orc.som_pass_eq(W, C, L, v, 1)).all()
