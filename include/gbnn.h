@@ -153,6 +153,31 @@ int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes
                           int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sparse form W' of W (Section IV-B, "Sparsification": only the nonzero elements and their
+ * coordinates are kept) and sum-of-max retrieval from W' alone.  W' is one caller-owned device
+ * buffer, 256-byte aligned: uint32_t offsets[n+1], then, each at the next multiple of 256 bytes, the
+ * C cluster summary rows of gbnn_prepare with their flags (256 bytes) and uint16_t cols[] to the end
+ * of the buffer; the neighbours of neuron i are cols[offsets[i] .. offsets[i+1]), ascending neuron
+ * numbers.  It pays where a list is shorter than a packed row (2 bytes per edge against n/8 per
+ * row: densities below 1/16) and W no longer fits the caches.  Shapes: L a multiple of 32.
+ *
+ * gbnn_sparse_count   *nnz_out (device) = number of nonzero elements of W, i.e. the entries cols
+ *                     needs.  Read it back, then size W' with gbnn_sparse_bytes.
+ * gbnn_sparse_bytes   bytes of a W' with room for nnz entries; 0 for arguments outside the limits
+ *                     (nnz < 2^32).
+ * gbnn_sparsify       fills W' from W.  status: device int32_t or NULL; bit 0 is OR-ed in if the
+ *                     buffer is too small for all entries -- W' must then not be used for
+ *                     retrieval (the call itself stays within the buffer).  Zero it before.
+ * gbnn_retrieve_sparse  gbnn_retrieve_symbols with rule GBNN_SUM_OF_MAX (Eq. 6-7) reading W'
+ *                     instead of W and a workspace: same probes, outputs, pass counts and results.
+ */
+size_t gbnn_sparse_bytes(int C, int L, int64_t nnz);
+int gbnn_sparse_count(const uint32_t *W, int C, int L, uint64_t *nnz_out, void *stream);
+int gbnn_sparsify(const uint32_t *W, int C, int L, void *Wp, size_t Wp_bytes, int32_t *status, void *stream);
+int gbnn_retrieve_sparse(const void *Wp, size_t Wp_bytes, int C, int L, const int32_t *probes, int64_t K,
+                         int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out, void *stream);
+
 /* Static description of a status code (never NULL). */
 const char *gbnn_strerror(int code);
 

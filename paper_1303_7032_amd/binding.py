@@ -53,6 +53,14 @@ def lib() -> ctypes.CDLL:
         L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
         L.gbnn_retrieve_symbols.restype = ci
         L.gbnn_retrieve_symbols.argtypes = [vp, ci, ci, vp, i64, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        L.gbnn_sparse_bytes.restype = sz
+        L.gbnn_sparse_bytes.argtypes = [ci, ci, i64]
+        L.gbnn_sparse_count.restype = ci
+        L.gbnn_sparse_count.argtypes = [vp, ci, ci, vp, vp]
+        L.gbnn_sparsify.restype = ci
+        L.gbnn_sparsify.argtypes = [vp, ci, ci, vp, sz, vp, vp]
+        L.gbnn_retrieve_sparse.restype = ci
+        L.gbnn_retrieve_sparse.argtypes = [vp, sz, ci, ci, vp, i64, ci, vp, vp, vp, vp]
         L.gbnn_strerror.restype = ctypes.c_char_p
         L.gbnn_strerror.argtypes = [ci]
         L.gbnn_retrieve_path.restype = ctypes.c_char_p
@@ -226,3 +234,64 @@ def gbnn_retrieve_path(C: int, L: int, rule, V0: torch.Tensor | None = None, V_o
     p = lib().gbnn_retrieve_path(C, L, _rule(rule), V0.data_ptr() if V0 is not None else 0,
                                  V_out.data_ptr() if V_out is not None else 0)
     return p.decode() if p else ""
+
+
+def gbnn_sparse_bytes(C: int, L: int, nnz: int) -> int:
+    return int(lib().gbnn_sparse_bytes(C, L, nnz))
+
+
+def gbnn_sparse_count(W: torch.Tensor, C: int, L: int) -> int:
+    """Number of nonzero elements of W (synchronises: the count is read back)."""
+    _dev(W, torch.int32, "W")
+    if W.numel() * 4 != gbnn_w_bytes(C, L):
+        _check(ERRORS["SHAPE"])
+    out = torch.empty(1, dtype=torch.int64, device=W.device)
+    _check(lib().gbnn_sparse_count(W.data_ptr(), C, L, out.data_ptr(), _stream(W)))
+    return int(out.item())
+
+
+def gbnn_sparsify(W: torch.Tensor, C: int, L: int, Wp: torch.Tensor | None = None,
+                  status: torch.Tensor | None = None) -> torch.Tensor:
+    """Fill (and, if not supplied, size and allocate) the sparse form W' of W; returns it (uint8 tensor)."""
+    _dev(W, torch.int32, "W")
+    if W.numel() * 4 != gbnn_w_bytes(C, L):
+        _check(ERRORS["SHAPE"])
+    if Wp is None:
+        need = gbnn_sparse_bytes(C, L, gbnn_sparse_count(W, C, L))
+        if need == 0:
+            _check(ERRORS["SHAPE"])
+        Wp = torch.empty(need, dtype=torch.uint8, device=W.device)
+    _dev(Wp, torch.uint8, "Wp")
+    st = 0
+    if status is not None:
+        _dev(status, torch.int32, "status")
+        st = status.data_ptr()
+    _check(lib().gbnn_sparsify(W.data_ptr(), C, L, Wp.data_ptr(), Wp.numel(), st, _stream(W)))
+    return Wp
+
+
+def gbnn_retrieve_sparse(Wp: torch.Tensor, C: int, L: int, probes: torch.Tensor, max_iters: int = 20,
+                         bits_out: torch.Tensor | None = None, symbols_out: torch.Tensor | None = None,
+                         iters_out: torch.Tensor | None = None):
+    """Sum-of-max retrieval of probes (int32[K][C], -1 = erased) from the sparse W'.
+    Returns (bits_out int32[K][nw], symbols_out int32[K][C], iters_out int32[K])."""
+    _dev(Wp, torch.uint8, "Wp")
+    _dev(probes, torch.int32, "probes")
+    if probes.numel() % C:
+        _check(ERRORS["SHAPE"])
+    K = probes.numel() // C
+    nw = gbnn_w_row_words(C, L)
+    if bits_out is None:
+        bits_out = torch.empty((K, nw), dtype=torch.int32, device=probes.device)
+    if symbols_out is None:
+        symbols_out = torch.empty((K, C), dtype=torch.int32, device=probes.device)
+    if iters_out is None:
+        iters_out = torch.empty(K, dtype=torch.int32, device=probes.device)
+    for t, cnt, name in ((bits_out, K * nw, "bits_out"), (symbols_out, K * C, "symbols_out"), (iters_out, K, "iters_out")):
+        _dev(t, torch.int32, name)
+        if t.numel() != cnt:
+            _check(ERRORS["SHAPE"])
+    _check(lib().gbnn_retrieve_sparse(Wp.data_ptr(), Wp.numel(), C, L, probes.data_ptr() if K else 0, K, max_iters,
+                                      bits_out.data_ptr() if K else 0, symbols_out.data_ptr() if K else 0,
+                                      iters_out.data_ptr() if K else 0, _stream(Wp)))
+    return bits_out, symbols_out, iters_out

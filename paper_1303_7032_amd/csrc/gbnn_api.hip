@@ -161,6 +161,46 @@ int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes
     return retrieve_common(a, W, C, L, K, rule, gamma, max_iters, iters_out, workspace, workspace_bytes, stream);
 }
 
+size_t gbnn_sparse_bytes(int C, int L, int64_t nnz)
+{
+    if (!shape_ok(C, L) || L % 32 != 0 || nnz < 0 || nnz > 0xFFFFFFFFll) return 0;
+    const int n = C * L;
+    return sparse_cols_offset(C, n, (int)gbnn_w_row_words(C, L)) + (((size_t)nnz * 2 + 255) & ~(size_t)255);
+}
+
+int gbnn_sparse_count(const uint32_t *W, int C, int L, uint64_t *nnz_out, void *stream)
+{
+    if (!shape_ok(C, L)) return GBNN_ERR_SHAPE;
+    if (!W || !nnz_out) return GBNN_ERR_NULL;
+    const hipError_t e = launch_sparse_count(W, C * L, (int)gbnn_w_row_words(C, L),
+                                             reinterpret_cast<unsigned long long *>(nnz_out),
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+int gbnn_sparsify(const uint32_t *W, int C, int L, void *Wp, size_t Wp_bytes, int32_t *status, void *stream)
+{
+    if (!shape_ok(C, L) || L % 32 != 0) return GBNN_ERR_SHAPE;
+    if (!W) return GBNN_ERR_NULL;
+    if (!Wp || !aligned(Wp, 256) || Wp_bytes < gbnn_sparse_bytes(C, L, 0)) return GBNN_ERR_WORKSPACE;
+    const hipError_t e = launch_sparsify(W, C, L, (int)gbnn_w_row_words(C, L), static_cast<char *>(Wp), Wp_bytes,
+                                         status, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+int gbnn_retrieve_sparse(const void *Wp, size_t Wp_bytes, int C, int L, const int32_t *probes, int64_t K,
+                         int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out, void *stream)
+{
+    if (!shape_ok(C, L) || L % 32 != 0 || K < 0 || K > GBNN_MAX_K) return GBNN_ERR_SHAPE;
+    if (max_iters < 1) return GBNN_ERR_ITERS;
+    if (K > 0 && !probes) return GBNN_ERR_NULL;
+    if (!Wp || !aligned(Wp, 256) || Wp_bytes < gbnn_sparse_bytes(C, L, 0)) return GBNN_ERR_WORKSPACE;
+    const hipError_t e = launch_retrieve_sparse(static_cast<const char *>(Wp), Wp_bytes, C, L,
+                                                (int)gbnn_w_row_words(C, L), probes, K, max_iters, bits_out,
+                                                symbols_out, iters_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
 const char *gbnn_strerror(int code)
 {
     switch (code) {

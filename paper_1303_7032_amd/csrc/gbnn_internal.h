@@ -55,6 +55,20 @@ hipError_t launch_store_update(uint32_t *W, int C, int L, int nw, const int32_t 
                                uint32_t *has, uint32_t *Wb, uint64_t *full, hipStream_t s);
 hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
                           hipStream_t s);
+// The cluster summaries of W and the flags "row c is all ones" (part of gbnn_prepare and of gbnn_sparsify).
+hipError_t launch_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint64_t *full, hipStream_t s);
+
+// Sparse W': byte offsets of its parts (offsets at 0), and the launchers.
+size_t sparse_summary_offset(int n);
+size_t sparse_full_offset(int C, int n, int nw);
+size_t sparse_cols_offset(int C, int n, int nw);
+hipError_t launch_sparse_count(const uint32_t *W, int n, int nw, unsigned long long *total, hipStream_t s);
+hipError_t launch_sparsify(const uint32_t *W, int C, int L, int nw, char *Wp, size_t Wp_bytes, int32_t *status,
+                           hipStream_t s);
+hipError_t launch_retrieve_sparse(const char *Wp, size_t Wp_bytes, int C, int L, int nw, const int32_t *probes,
+                                  int64_t K, int max_iters, uint32_t *bits_out, int32_t *sym_out, int32_t *iters,
+                                  hipStream_t s);
+
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s);
 hipError_t launch_retrieve_half(const RetrieveArgs &a, hipStream_t s);
 hipError_t launch_retrieve_generic(const RetrieveArgs &a, hipStream_t s);

@@ -1,0 +1,362 @@
+// Sparse form W' of the adjacency (Section IV-B, "Sparsification": only the nonzero elements and their
+// coordinates) and sum-of-max retrieval (Eq. 6-7) from W' alone, for messages at the boundary.
+//
+// W' is one caller-owned buffer:
+//   offsets  uint32[n + 1]   neighbours of neuron i are cols[offsets[i] .. offsets[i+1])
+//   summary  uint32[C][nw]   bit i of row c: i is in c or has a neighbour in c (what a fully active
+//                            cluster lets survive), followed by one uint64 of flags: row c is all ones
+//   cols     uint16[...]     neuron numbers, ascending within a list; to the end of the buffer
+// Retrieval: one wavefront per probe.  The activity vector lives in registers (word w in lane w % 64);
+// a pass walks the clusters whose active set changed in the pass before (Lemma 1: the others cannot
+// switch anything off).  A fully active cluster contributes its summary row; any other cluster c has the
+// neighbour lists of its active neurons scattered into a bit vector T in LDS (one lane per list entry,
+// ds_or), and every neuron outside c that is not in T goes off.  The state and the number of passes are
+// those of the kernels that read the packed W.
+#include "gbnn_device.h"
+#include "gbnn_internal.h"
+
+namespace gbnn {
+namespace {
+
+constexpr int kSparseMaxWords = GBNN_MAX_N / 32;       // packed words of an activity vector, at most
+constexpr int kSparseSlots = kSparseMaxWords / 64;     // ... per lane
+constexpr int kSparseWaves = 4;                        // probes per workgroup
+
+// LDS traffic between the lanes of one wave: make earlier writes visible to later reads.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
+{
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s, 64);
+    return x;
+}
+
+// total = number of set bits of W.  One wave per row, then one atomic add per row.
+__global__ __launch_bounds__(64) void k_sparse_zero(unsigned long long *total) { if (threadIdx.x == 0) *total = 0ull; }
+__global__ __launch_bounds__(256) void k_sparse_total(const uint32_t *__restrict__ W, int n, int nw,
+                                                      unsigned long long *total)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
+    uint32_t pc = 0;
+    for (int w = lane; w < nw; w += 64) pc += __popc(W[(int64_t)i * nw + w]);
+    pc = wave_sum(pc);
+    if (lane == 0 && pc) atomicAdd(total, (unsigned long long)pc);
+}
+
+// offsets[i + 1] = degree of neuron i (offsets[0] = 0); one wave per row.
+__global__ __launch_bounds__(256) void k_sparse_degree(const uint32_t *__restrict__ W, int n, int nw,
+                                                       uint32_t *__restrict__ offsets)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
+    uint32_t pc = 0;
+    for (int w = lane; w < nw; w += 64) pc += __popc(W[(int64_t)i * nw + w]);
+    pc = wave_sum(pc);
+    if (lane == 0) {
+        offsets[i + 1] = pc;
+        if (i == 0) offsets[0] = 0u;
+    }
+}
+
+// In-place inclusive scan of offsets[1..n] by one workgroup: every thread sums a run of consecutive
+// entries, the run totals are scanned in LDS, then every thread rewrites its run.
+__global__ __launch_bounds__(1024) void k_sparse_scan(uint32_t *__restrict__ offsets, int n, uint32_t capacity,
+                                                      int32_t *__restrict__ status)
+{
+    __shared__ uint32_t part[1024];
+    const int run = (n + 1023) / 1024;
+    const int lo = threadIdx.x * run;
+    const int hi = lo + run < n ? lo + run : n;
+    uint32_t sum = 0;
+    for (int i = lo; i < hi; ++i) sum += offsets[i + 1];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int s = 1; s < 1024; s <<= 1) {
+        const uint32_t add = threadIdx.x >= (unsigned)s ? part[threadIdx.x - s] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t acc = part[threadIdx.x] - sum;
+    for (int i = lo; i < hi; ++i) {
+        acc += offsets[i + 1];
+        offsets[i + 1] = acc;
+    }
+    if (threadIdx.x == 1023 && part[1023] > capacity && status) atomicOr(status, 1);
+}
+
+// cols[offsets[i] ..] = the set bits of row i, ascending; one wave per row, 64 words at a time.  Entries
+// beyond the capacity of the buffer are not written (the scan has reported that case).
+__global__ __launch_bounds__(256) void k_sparse_fill(const uint32_t *__restrict__ W, int n, int nw,
+                                                     const uint32_t *__restrict__ offsets,
+                                                     uint16_t *__restrict__ cols, uint32_t capacity)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
+    uint32_t at = offsets[i];
+    for (int w0 = 0; w0 < nw; w0 += 64) {
+        const int w = w0 + lane;
+        uint32_t word = w < nw ? W[(int64_t)i * nw + w] : 0u;
+        const uint32_t pc = __popc(word);
+        uint32_t before = pc;  // inclusive prefix sum over the lanes
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const uint32_t up = __shfl_up(before, s, 64);
+            if (lane >= s) before += up;
+        }
+        const uint32_t total = __shfl(before, 63, 64);
+        uint32_t pos = at + before - pc;
+        while (word) {
+            const int b = __builtin_ctz(word);
+            word &= word - 1u;
+            if (pos < capacity) cols[pos] = (uint16_t)(w * 32 + b);
+            ++pos;
+        }
+        at += total;
+    }
+}
+
+struct SparseArgs {
+    const uint32_t *offsets;
+    const uint32_t *summary;
+    const uint64_t *full;
+    const uint16_t *cols;
+    uint32_t capacity;
+    const int32_t *sym_in;
+    uint32_t *bits_out;
+    int32_t *sym_out;
+    int32_t *iters;
+    int64_t K;
+    int C, L, nw, wpc;  // wpc = L / 32 words per cluster
+    int max_iters;
+};
+
+__global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArgs a)
+{
+    __shared__ uint32_t lds[kSparseWaves][2][kSparseMaxWords];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t k = (int64_t)blockIdx.x * kSparseWaves + wave;
+    if (k >= a.K) return;  // the whole wave
+    uint32_t *cur = lds[wave][0];
+    uint32_t *T = lds[wave][1];
+    const int nw = a.nw, wpc = a.wpc, C = a.C, L = a.L;
+    const uint64_t summary_full = *a.full;
+
+    // word w = lane + 64 u of the activity vector; its cluster; Section III-C: an erased cluster starts
+    // with all of its neurons on, a known one with the neuron of its symbol
+    uint32_t v[kSparseSlots], d[kSparseSlots], acc[kSparseSlots];
+    int cl[kSparseSlots];
+#pragma unroll
+    for (int u = 0; u < kSparseSlots; ++u) {
+        const int w = lane + 64 * u;
+        cl[u] = w < nw ? w / wpc : -1;
+        v[u] = 0u;
+        d[u] = 0u;
+        if (w < nw) {
+            const int32_t s = a.sym_in[k * C + cl[u]];
+            const int wi = w - cl[u] * wpc;
+            v[u] = (uint32_t)s < (uint32_t)L ? ((s >> 5) == wi ? 1u << (s & 31) : 0u) : 0xFFFFFFFFu;
+        }
+    }
+
+    int32_t iters = 0;
+    for (int p = 1;; ++p) {
+        // per cluster: number of active neurons, and whether any changed in the pass before
+#pragma unroll
+        for (int u = 0; u < kSparseSlots; ++u) {
+            const int w = lane + 64 * u;
+            if (w < nw) {
+                cur[w] = v[u];
+                T[w] = d[u];
+            }
+        }
+        wave_lds_sync();
+        uint32_t cnt = 0, chg = 0;
+        if (lane < C) {
+            for (int i = 0; i < wpc; ++i) {
+                cnt += __popc(cur[lane * wpc + i]);
+                chg |= T[lane * wpc + i];
+            }
+        }
+        const uint64_t emptym = ballot(lane < C && cnt == 0u);
+        const uint64_t fullm = ballot(lane < C && cnt == (uint32_t)L);
+        uint64_t srcm = p == 1 ? ballot(lane < C) : ballot(lane < C && chg != 0u);
+        wave_lds_sync();
+#pragma unroll
+        for (int u = 0; u < kSparseSlots; ++u) acc[u] = emptym ? 0u : v[u];
+        if (emptym) srcm = 0;  // a cluster without an active neuron: nobody reaches C - 1 clusters
+        while (srcm) {
+            const int c = __builtin_ctzll(srcm);
+            srcm &= srcm - 1ull;
+            if ((fullm >> c) & 1ull) {
+                if (!((summary_full >> c) & 1ull)) {
+#pragma unroll
+                    for (int u = 0; u < kSparseSlots; ++u) {
+                        const int w = lane + 64 * u;
+                        if (w < nw) acc[u] &= a.summary[(int64_t)c * nw + w];
+                    }
+                }
+                continue;
+            }
+#pragma unroll
+            for (int u = 0; u < kSparseSlots; ++u) {
+                const int w = lane + 64 * u;
+                if (w < nw) T[w] = 0u;
+            }
+            wave_lds_sync();
+            for (int i0 = 0; i0 < wpc; i0 += 64) {
+                const uint32_t word = i0 + lane < wpc ? cur[c * wpc + i0 + lane] : 0u;
+                uint64_t holders = ballot(word != 0u);
+                while (holders) {
+                    const int l = __builtin_ctzll(holders);
+                    holders &= holders - 1ull;
+                    uint32_t bits = readlane(word, l);
+                    while (bits) {
+                        const int b = __builtin_ctz(bits);
+                        bits &= bits - 1u;
+                        const int j = c * L + (i0 + l) * 32 + b;
+                        const uint32_t beg = a.offsets[j];
+                        uint32_t end = a.offsets[j + 1];
+                        end = end < a.capacity ? end : a.capacity;
+                        for (uint32_t t = beg + lane; t < end; t += 64) {
+                            const uint32_t col = a.cols[t];
+                            atomicOr(&T[col >> 5], 1u << (col & 31));
+                        }
+                    }
+                }
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int u = 0; u < kSparseSlots; ++u) {
+                const int w = lane + 64 * u;
+                if (w < nw && cl[u] != c) acc[u] &= T[w];
+            }
+            wave_lds_sync();
+        }
+        bool changed = false;
+#pragma unroll
+        for (int u = 0; u < kSparseSlots; ++u) {
+            d[u] = acc[u] ^ v[u];
+            changed = changed || d[u] != 0u;
+            v[u] = acc[u];
+        }
+        const bool any = ballot(changed) != 0ull;
+        if (!any) {
+            iters = p;
+            break;
+        }
+        if (p == a.max_iters) {
+            iters = -p;
+            break;
+        }
+    }
+
+    if (a.iters && lane == 0) a.iters[k] = iters;
+    if (a.bits_out) {
+#pragma unroll
+        for (int u = 0; u < kSparseSlots; ++u) {
+            const int w = lane + 64 * u;
+            if (w < nw) a.bits_out[k * nw + w] = v[u];
+        }
+    }
+    if (a.sym_out) {
+#pragma unroll
+        for (int u = 0; u < kSparseSlots; ++u) {
+            const int w = lane + 64 * u;
+            if (w < nw) cur[w] = v[u];
+        }
+        wave_lds_sync();
+        if (lane < C) {
+            uint32_t cnt = 0;
+            int32_t pos = 0;
+            for (int i = 0; i < wpc; ++i) {
+                const uint32_t word = cur[lane * wpc + i];
+                if (word && !cnt) pos = i * 32 + __builtin_ctz(word);
+                cnt += __popc(word);
+            }
+            a.sym_out[k * C + lane] = cnt == 1u ? pos : (cnt == 0u ? GBNN_SYM_NONE : GBNN_SYM_AMBIGUOUS);
+        }
+    }
+}
+
+}  // namespace
+
+size_t sparse_summary_offset(int n) { return (((size_t)n + 1) * sizeof(uint32_t) + 255) & ~(size_t)255; }
+size_t sparse_full_offset(int C, int n, int nw)
+{
+    return sparse_summary_offset(n) + (((size_t)C * nw * sizeof(uint32_t) + 255) & ~(size_t)255);
+}
+size_t sparse_cols_offset(int C, int n, int nw) { return sparse_full_offset(C, n, nw) + 256; }
+
+hipError_t launch_sparse_count(const uint32_t *W, int n, int nw, unsigned long long *total, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_sparse_zero, dim3(1), dim3(64), 0, s, total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_sparse_total, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, W, n, nw, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparsify(const uint32_t *W, int C, int L, int nw, char *Wp, size_t Wp_bytes, int32_t *status,
+                           hipStream_t s)
+{
+    const int n = C * L;
+    uint32_t *offsets = reinterpret_cast<uint32_t *>(Wp);
+    uint32_t *summary = reinterpret_cast<uint32_t *>(Wp + sparse_summary_offset(n));
+    uint64_t *full = reinterpret_cast<uint64_t *>(Wp + sparse_full_offset(C, n, nw));
+    uint16_t *cols = reinterpret_cast<uint16_t *>(Wp + sparse_cols_offset(C, n, nw));
+    const size_t room = (Wp_bytes - sparse_cols_offset(C, n, nw)) / sizeof(uint16_t);
+    const uint32_t capacity = room > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)room;
+    const dim3 rows((unsigned)((n + 3) / 4));
+    hipLaunchKernelGGL(k_sparse_degree, rows, dim3(256), 0, s, W, n, nw, offsets);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_sparse_scan, dim3(1), dim3(1024), 0, s, offsets, n, capacity, status);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_sparse_fill, rows, dim3(256), 0, s, W, n, nw, offsets, cols, capacity);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_summary(W, C, L, nw, summary, full, s);
+}
+
+hipError_t launch_retrieve_sparse(const char *Wp, size_t Wp_bytes, int C, int L, int nw, const int32_t *probes,
+                                  int64_t K, int max_iters, uint32_t *bits_out, int32_t *sym_out, int32_t *iters,
+                                  hipStream_t s)
+{
+    if (K == 0) return hipSuccess;
+    const int n = C * L;
+    SparseArgs a{};
+    a.offsets = reinterpret_cast<const uint32_t *>(Wp);
+    a.summary = reinterpret_cast<const uint32_t *>(Wp + sparse_summary_offset(n));
+    a.full = reinterpret_cast<const uint64_t *>(Wp + sparse_full_offset(C, n, nw));
+    a.cols = reinterpret_cast<const uint16_t *>(Wp + sparse_cols_offset(C, n, nw));
+    const size_t room = (Wp_bytes - sparse_cols_offset(C, n, nw)) / sizeof(uint16_t);
+    a.capacity = room > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)room;
+    a.sym_in = probes;
+    a.bits_out = bits_out;
+    a.sym_out = sym_out;
+    a.iters = iters;
+    a.K = K;
+    a.C = C;
+    a.L = L;
+    a.nw = nw;
+    a.wpc = L / 32;
+    a.max_iters = max_iters;
+    const int64_t blocks = (K + kSparseWaves - 1) / kSparseWaves;
+    hipLaunchKernelGGL(k_retrieve_sparse, dim3((unsigned)blocks), dim3(64 * kSparseWaves), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace gbnn

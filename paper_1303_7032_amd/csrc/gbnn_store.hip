@@ -304,15 +304,20 @@ hipError_t launch_store_update(uint32_t *W, int C, int L, int nw, const int32_t 
     return hipGetLastError();
 }
 
-hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
-                          hipStream_t s)
+hipError_t launch_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint64_t *full, hipStream_t s)
 {
     dim3 grid((unsigned)((nw + 63) / 64), (unsigned)C);
     hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, C * L, nw, full);
-    e = hipGetLastError();
+    return hipGetLastError();
+}
+
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
+                          hipStream_t s)
+{
+    const hipError_t e = launch_summary(W, C, L, nw, has, full, s);
     if (e != hipSuccess) return e;
     const int64_t words = (int64_t)C * L * nw;
     int64_t blocks = (words + 255) / 256;

@@ -111,6 +111,33 @@ def test_store_update_argument_errors(lib):
     assert lib.gbnn_store_update(0x1000, 8, 256, 0x1000, 1, 0, 0x10000, need - 1, 0) == E["WORKSPACE"]
 
 
+def test_sparse_sizes_and_argument_errors(lib):
+    E = gb.ERRORS
+    base = gb.gbnn_sparse_bytes(8, 256, 0)
+    assert base % 256 == 0 and base >= (2048 + 1) * 4 + 8 * 64 * 4 + 256
+    assert gb.gbnn_sparse_bytes(8, 256, 1) == base + 256 and gb.gbnn_sparse_bytes(8, 256, 129) == base + 512
+    assert gb.gbnn_sparse_bytes(8, 100, 0) == 0          # L must be a multiple of 32
+    assert gb.gbnn_sparse_bytes(8, 256, -1) == 0 and gb.gbnn_sparse_bytes(8, 256, 1 << 32) == 0
+    assert gb.gbnn_sparse_bytes(1, 256, 0) == 0
+    assert lib.gbnn_sparse_count(0, 8, 256, 0x1000, 0) == E["NULL"]
+    assert lib.gbnn_sparse_count(0x1000, 8, 256, 0, 0) == E["NULL"]
+    assert lib.gbnn_sparse_count(0x1000, 1, 256, 0x1000, 0) == E["SHAPE"]
+    assert lib.gbnn_sparsify(0x1000, 8, 100, 0x10000, 1 << 20, 0, 0) == E["SHAPE"]
+    assert lib.gbnn_sparsify(0, 8, 256, 0x10000, 1 << 20, 0, 0) == E["NULL"]
+    assert lib.gbnn_sparsify(0x1000, 8, 256, 0, 1 << 20, 0, 0) == E["WORKSPACE"]
+    assert lib.gbnn_sparsify(0x1000, 8, 256, 0x10010, 1 << 20, 0, 0) == E["WORKSPACE"]
+    assert lib.gbnn_sparsify(0x1000, 8, 256, 0x10000, base - 1, 0, 0) == E["WORKSPACE"]
+    ok = (0x10000, base, 8, 256, 0x1000, 1, 20, 0, 0, 0, 0)
+    assert lib.gbnn_retrieve_sparse(0x10000, base, 8, 100, 0x1000, 1, 20, 0, 0, 0, 0) == E["SHAPE"]
+    assert lib.gbnn_retrieve_sparse(0x10000, base, 8, 256, 0x1000, -1, 20, 0, 0, 0, 0) == E["SHAPE"]
+    assert lib.gbnn_retrieve_sparse(0x10000, base, 8, 256, 0x1000, 1, 0, 0, 0, 0, 0) == E["ITERS"]
+    assert lib.gbnn_retrieve_sparse(0x10000, base, 8, 256, 0, 1, 20, 0, 0, 0, 0) == E["NULL"]
+    assert lib.gbnn_retrieve_sparse(0, base, 8, 256, 0x1000, 1, 20, 0, 0, 0, 0) == E["WORKSPACE"]
+    assert lib.gbnn_retrieve_sparse(0x10000, base - 1, 8, 256, 0x1000, 1, 20, 0, 0, 0, 0) == E["WORKSPACE"]
+    assert lib.gbnn_retrieve_sparse(0x10000, base, 8, 256, 0, 0, 20, 0, 0, 0, 0) == 0   # K = 0: nothing to do
+    del ok
+
+
 def test_strerror_and_path(lib):
     for code in range(-8, 1):
         assert gb.gbnn_strerror(code)
