@@ -37,18 +37,24 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
     return x;
 }
 
-// total = number of set bits of W.  One wave per row, then one atomic add per row.
+// total = number of set bits of W: every thread strides over the words; one atomic add per workgroup
+// (atomics on one address are served one after the other, so there are few workgroups).
 __global__ __launch_bounds__(64) void k_sparse_zero(unsigned long long *total) { if (threadIdx.x == 0) *total = 0ull; }
-__global__ __launch_bounds__(256) void k_sparse_total(const uint32_t *__restrict__ W, int n, int nw,
-                                                      unsigned long long *total)
+__global__ __launch_bounds__(1024) void k_sparse_total(const uint32_t *__restrict__ W, int64_t words,
+                                                       unsigned long long *total)
 {
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (i >= n) return;
-    uint32_t pc = 0;
-    for (int w = lane; w < nw; w += 64) pc += __popc(W[(int64_t)i * nw + w]);
+    __shared__ uint32_t part[16];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    uint32_t pc = 0;  // at most 32 * words / stride per thread: no overflow within the shape limits
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < words; t += stride) pc += __popc(W[t]);
     pc = wave_sum(pc);
-    if (lane == 0 && pc) atomicAdd(total, (unsigned long long)pc);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = pc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long sum = 0;
+        for (int i = 0; i < 16; ++i) sum += part[i];
+        if (sum) atomicAdd(total, sum);
+    }
 }
 
 // offsets[i + 1] = degree of neuron i (offsets[0] = 0); one wave per row.
@@ -229,9 +235,18 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
                         const uint32_t beg = a.offsets[j];
                         uint32_t end = a.offsets[j + 1];
                         end = end < a.capacity ? end : a.capacity;
-                        for (uint32_t t = beg + lane; t < end; t += 64) {
-                            const uint32_t col = a.cols[t];
-                            atomicOr(&T[col >> 5], 1u << (col & 31));
+                        // four loads in flight per lane before the first of them is needed
+                        // (entry numbers stay far below 2^32: at most n * n of them)
+                        for (uint32_t t0 = beg; t0 < end; t0 += 256) {
+                            uint32_t col[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const uint32_t t = t0 + 64u * q + lane;
+                                col[q] = t < end ? (uint32_t)a.cols[t] : 0xFFFFFFFFu;
+                            }
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (col[q] != 0xFFFFFFFFu) atomicOr(&T[col[q] >> 5], 1u << (col[q] & 31));
                         }
                     }
                 }
@@ -304,7 +319,10 @@ hipError_t launch_sparse_count(const uint32_t *W, int n, int nw, unsigned long l
     hipLaunchKernelGGL(k_sparse_zero, dim3(1), dim3(64), 0, s, total);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_sparse_total, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, W, n, nw, total);
+    const int64_t words = (int64_t)n * nw;
+    int64_t blocks = (words + 1023) / 1024;
+    if (blocks > 64) blocks = 64;
+    hipLaunchKernelGGL(k_sparse_total, dim3((unsigned)blocks), dim3(1024), 0, s, W, words, total);
     return hipGetLastError();
 }
 
