@@ -171,8 +171,19 @@ template <int NW, int B>
 __device__ __forceinline__ void and_batch(const Ctx<NW> &x, uint32_t offv, int i0, uint32_t (&acc)[NW])
 {
     uint32_t r[B][NW];
+    // a lane with nothing left on does not need its word of the rows (and then fetches nothing: half of
+    // the row bytes for the hybrid rule, whose known clusters are not updated)
 #pragma unroll
-    for (int q = 0; q < B; ++q) load_row(x, x.wbrsrc, readlane(offv, i0 + q), r[q]);
+    for (int u = 0; u < NW; ++u) {
+        if (acc[u] != 0u) {
+#pragma unroll
+            for (int q = 0; q < B; ++q)
+                r[q][u] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, x.woffb[u], readlane(offv, i0 + q), 0);
+        } else {
+#pragma unroll
+            for (int q = 0; q < B; ++q) r[q][u] = 0u;
+        }
+    }
 #pragma unroll
     for (int q = 0; q < B; ++q)
 #pragma unroll
@@ -656,7 +667,7 @@ k_retrieve_wave(RetrieveArgs a)
                     uint64_t summask[NW];
 #pragma unroll
                     for (int t = 0; t < NW; ++t) {
-                        acc[t] = erased[t] ? 0xFFFFFFFFu : v[t];
+                        acc[t] = erased[t] ? 0xFFFFFFFFu : 0u;  // (known clusters are restored below: their lanes fetch nothing)
                         pw[t] = v[t];
                         summask[t] = 0;
                     }
