@@ -188,6 +188,30 @@ def main() -> int:
                                "hbm_bytes_per_launch": mb_bytes, "hbm_GBs": mb_bytes / (ms.mean() * 1e-3) / 1e9,
                                "same_pass_counts_as_activity_boundary": same}
 
+    # ---- sum-of-sum only: what one pass of the dense formulation S = W V (Eq. 8) costs as a library int8
+    # GEMM on the same batch (a reference point for the choice of the sparse bit-sliced form; not used by
+    # the path, and its output S would still need Eq. (4)-(5))
+    dense_product = None
+    if "sum_of_sum" in rules:
+        try:
+            shifts = torch.arange(32, device="cuda", dtype=torch.int32)
+            W8 = ((W.view(n, nw, 1) >> shifts) & 1).reshape(n, nw * 32)[:, :n].to(torch.int8).contiguous()
+            V8 = V0d.t().contiguous().view(torch.int8)
+            for _ in range(2):
+                S = torch._int_mm(W8, V8)
+            ge = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+            for a_, b_ in ge:
+                a_.record()
+                S = torch._int_mm(W8, V8)
+                b_.record()
+            torch.cuda.synchronize()
+            us = float(np.median([a_.elapsed_time(b_) for a_, b_ in ge])) * 1e3
+            dense_product = {"what": "torch._int_mm(W int8[n][n], V int8[n][K]) -> int32[n][K], one pass, library GEMM",
+                             "us_per_pass": us, "int8_TOPs": 2.0 * n * n * K / (us * 1e-6) / 1e12}
+            del S, W8, V8
+        except Exception as exc:  # the library may lack the routine for this shape
+            dense_product = {"error": repr(exc)[:200]}
+
     if args.calibrate_copy:
         for _ in range(3):
             outs[rules[0]].view(torch.int64).copy_(V0d.view(torch.int64))  # 8-byte elements: full-width stores
@@ -252,6 +276,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "per_rule": per_rule,
         "message_boundary": message_boundary,
+        "dense_product_reference": dense_product,
         "store": {"messages": w.M, "seconds_incl_launch_and_sync": store_s, "event_us": store_event_us,
                   "messages_per_second": w.M / (store_event_us * 1e-6),
                   "prepare_seconds_incl_launch_and_sync": prepare_s},
