@@ -185,7 +185,11 @@ const char *gbnn_strerror(int code);
  * ("half1" = two probes per wavefront, one packed word per lane, networks of up to 1024 neurons;
  * "wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
  * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the family
- * reported for V0 = V_out = NULL.  Host only; for tests and reports. */
+ * reported for V0 = V_out = NULL.  Host only; for tests and reports.
+ * The register-resident families need L to be a power of two in 32..2048 and n <= 8192; the any-shape
+ * kernel is more than ten times slower.  A network whose L is not a power of two can be stored with L
+ * rounded up (the extra neurons are never part of a message): retrieval then returns the same symbols,
+ * and pass counts that can be larger by the pass that switches the extra neurons off. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
 
 #ifdef __cplusplus
