@@ -159,8 +159,9 @@ int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes
  * buffer, 256-byte aligned: uint32_t offsets[n+1], then, each at the next multiple of 256 bytes, the
  * C cluster summary rows of gbnn_prepare with their flags (256 bytes) and uint16_t cols[] to the end
  * of the buffer; the neighbours of neuron i are cols[offsets[i] .. offsets[i+1]), ascending neuron
- * numbers.  It pays where a list is shorter than a packed row (2 bytes per edge against n/8 per
- * row: densities below 1/16) and W no longer fits the caches.  Shapes: L a multiple of 32.
+ * numbers.  A list is shorter than a packed row below a density of 1/16 (2 bytes per edge against
+ * n/8 per row); it is the faster form only for shapes that gbnn_retrieve_path reports as "generic".
+ * Shapes: L a multiple of 32.
  *
  * gbnn_sparse_count   *nnz_out (device) = number of nonzero elements of W, i.e. the entries cols
  *                     needs.  Read it back, then size W' with gbnn_sparse_bytes.
@@ -183,10 +184,11 @@ const char *gbnn_strerror(int code);
 
 /* Name of the kernel family gbnn_retrieve would run for this shape, rule and pointer alignment
  * ("half1" = two probes per wavefront, one packed word per lane, networks of up to 1024 neurons;
- * "wave1", "wave2", "wave4" = one wavefront per probe with 1, 2 or 4 packed words per lane;
+ * "wave1", "wave2", "wave4", "wave8" = one wavefront per probe with 1, 2, 4 or 8 packed words per lane;
  * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the family
  * reported for V0 = V_out = NULL.  Host only; for tests and reports.
- * The register-resident families need L to be a power of two in 32..2048 and n <= 8192; the any-shape
+ * The register-resident families need L to be a power of two in 32..2048 and n <= 8192 (sum-of-max
+ * and hybrid: n <= 16384); the any-shape
  * kernel is more than ten times slower.  A network whose L is not a power of two can be stored with L
  * rounded up (the extra neurons are never part of a message): retrieval then returns the same symbols,
  * and pass counts that can be larger by the pass that switches the extra neurons off. */

@@ -19,11 +19,11 @@ bool rule_ok(int rule) { return rule == GBNN_SUM_OF_SUM || rule == GBNN_SUM_OF_M
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-// Kernel family for a call: 0 = any-shape kernel; 1, 2, 4 = one wavefront per probe with that many packed
+// Kernel family for a call: 0 = any-shape kernel; 1, 2, 4, 8 = one wavefront per probe with that many packed
 // words per lane; kHalfPath = half a wavefront per probe.  The environment variables GBNN_FORCE_GENERIC=1
 // and GBNN_FORCE_WAVE=1 (no half-wave kernel) exist for tests and A/B timing.
 constexpr int kHalfPath = 10;
-int pick_path(int C, int L, const void *V0, const void *Vout)
+int pick_path(int C, int L, int rule, const void *V0, const void *Vout)
 {
     const char *force = std::getenv("GBNN_FORCE_GENERIC");
     if (force && force[0] == '1') return 0;
@@ -32,7 +32,9 @@ int pick_path(int C, int L, const void *V0, const void *Vout)
     if (!(wave && wave[0] == '1')) {
         if (half_wave_serves(C, L)) return kHalfPath;
     }
-    return wave_words_per_lane(C, L);
+    const int words = wave_words_per_lane(C, L);
+    // eight words per lane: sum-of-max and hybrid only (the counters of sum-of-sum do not fit the registers)
+    return (words == 8 && rule == GBNN_SUM_OF_SUM) ? 0 : words;
 }
 
 // Checks common to both boundaries, then the launch.
@@ -56,7 +58,7 @@ int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K,
     a.gamma = gamma;
     a.max_iters = max_iters;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int path = pick_path(C, L, a.V0, a.Vout);
+    const int path = pick_path(C, L, rule, a.V0, a.Vout);
     const hipError_t e = path == kHalfPath ? launch_retrieve_half(a, s)
                          : path            ? launch_retrieve_wave(a, path, s)
                                            : launch_retrieve_generic(a, s);
@@ -219,10 +221,11 @@ const char *gbnn_strerror(int code)
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out)
 {
     if (!shape_ok(C, L) || !rule_ok(rule)) return nullptr;
-    switch (pick_path(C, L, V0, V_out)) {
+    switch (pick_path(C, L, rule, V0, V_out)) {
     case 1: return "wave1";
     case 2: return "wave2";
     case 4: return "wave4";
+    case 8: return "wave8";
     case kHalfPath: return "half1";
     default: return "generic";
     }

@@ -573,9 +573,10 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
 }
 
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
-// Register budget: 8 / 5 / 4 waves per SIMD at 1 / 2 / 4 words per lane (2 for sum-of-sum at 4).
+// Register budget, waves per SIMD: sum-of-max and hybrid 8 / 8 / 5 / 2 at 1 / 2 / 4 / 8 words per lane,
+// sum-of-sum 8 / 5 / 4 (not built at 8: its counters do not fit the registers).
 template <int NW, int RULE, int LG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : RULE == GBNN_SUM_OF_SUM ? 4 : 5))) void
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : NW == 8 ? 2 : RULE == GBNN_SUM_OF_SUM ? 4 : 5))) void
 k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
@@ -854,6 +855,32 @@ hipError_t launch_one(const RetrieveArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Eight words per lane (n up to 16384): sum-of-max and hybrid only, clusters of 8 to 64 lanes.
+template <int LG>
+hipError_t launch_one8(const RetrieveArgs &a, hipStream_t s)
+{
+    const int wpb = 4;
+    const int64_t blocks = (a.K + wpb - 1) / wpb;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(64 * wpb);
+    if (a.rule == GBNN_SUM_OF_SUM) return hipErrorInvalidValue;
+    if (a.rule == GBNN_SUM_OF_MAX)
+        hipLaunchKernelGGL((k_retrieve_wave<8, GBNN_SUM_OF_MAX, LG>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_retrieve_wave<8, GBNN_HYBRID, LG>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_nw8(const RetrieveArgs &a, int log2lw, hipStream_t s)
+{
+    switch (log2lw) {
+    case 3: return launch_one8<3>(a, s);
+    case 4: return launch_one8<4>(a, s);
+    case 5: return launch_one8<5>(a, s);
+    case 6: return launch_one8<6>(a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 template <int NW>
 hipError_t launch_nw(const RetrieveArgs &a, int log2lw, hipStream_t s)
 {
@@ -878,6 +905,7 @@ int wave_words_per_lane(int C, int L)
     if (nw <= 64) return 1;
     if (nw <= 128) return 2;
     if (nw <= 256) return 4;
+    if (nw <= 512) return 8;
     return 0;
 }
 
@@ -891,6 +919,7 @@ hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipSt
     case 1: return launch_nw<1>(a, log2lw, s);
     case 2: return launch_nw<2>(a, log2lw, s);
     case 4: return launch_nw<4>(a, log2lw, s);
+    case 8: return launch_nw8(a, log2lw, s);
     default: return hipErrorInvalidValue;
     }
 }

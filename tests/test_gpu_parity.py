@@ -148,7 +148,10 @@ SHAPES = [
     (12, 256, 20000, 6, 300),  # 96 words: two words per lane, second slot half empty
     (16, 512, 100000, 8, 260),  # cfg5 shape: four words per lane
     (2, 2048, 3000, 1, 70),  # a cluster is a whole wave
-    (16, 1024, 60000, 8, 20),  # n = 16384: the largest shape, any-shape kernel
+    (16, 1024, 60000, 8, 20),  # n = 16384, the largest: eight words per lane (sum-of-sum: any-shape kernel)
+    (8, 2048, 40000, 4, 40),   # ... a cluster is a whole slot
+    (64, 256, 8000, 32, 36),   # ... eight lanes per cluster
+    (9, 1024, 30000, 4, 33),   # 288 words: the fifth slot half empty
     (32, 32, 700, 16, 131),    # two probes per wave, a cluster is one lane, odd K
     (16, 64, 800, 8, 130),     # ... two lanes per cluster
     (2, 512, 30000, 1, 67),    # ... a cluster is half of the half-wave
