@@ -187,9 +187,8 @@ const char *gbnn_strerror(int code);
  * "wave1", "wave2", "wave4", "wave8" = one wavefront per probe with 1, 2, 4 or 8 packed words per lane;
  * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the family
  * reported for V0 = V_out = NULL.  Host only; for tests and reports.
- * The register-resident families need L to be a power of two in 32..2048 and n <= 8192 (sum-of-max
- * and hybrid: n <= 16384); the any-shape
- * kernel is more than ten times slower.  A network whose L is not a power of two can be stored with L
+ * The register-resident families need L to be a power of two in 32..2048 (every shape with such an
+ * L is within their reach); the any-shape kernel is more than ten times slower.  A network whose L is not a power of two can be stored with L
  * rounded up (the extra neurons are never part of a message): retrieval then returns the same symbols,
  * and pass counts that can be larger by the pass that switches the extra neurons off. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);

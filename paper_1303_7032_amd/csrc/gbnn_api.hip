@@ -32,9 +32,8 @@ int pick_path(int C, int L, int rule, const void *V0, const void *Vout)
     if (!(wave && wave[0] == '1')) {
         if (half_wave_serves(C, L)) return kHalfPath;
     }
-    const int words = wave_words_per_lane(C, L);
-    // eight words per lane: sum-of-max and hybrid only (the counters of sum-of-sum do not fit the registers)
-    return (words == 8 && rule == GBNN_SUM_OF_SUM) ? 0 : words;
+    (void)rule;
+    return wave_words_per_lane(C, L);
 }
 
 // Checks common to both boundaries, then the launch.

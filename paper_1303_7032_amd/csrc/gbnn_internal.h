@@ -40,8 +40,8 @@ inline size_t workspace_full_offset(int C, int L, int nw)
 }
 inline size_t workspace_total_bytes(int C, int L, int nw) { return workspace_full_offset(C, L, nw) + 256; }
 
-// Which kernel family serves a shape.  One wavefront per probe: packed words per lane (1, 2, 4; 8 for
-// sum-of-max and hybrid only), 0 = not served.  Half a wavefront per probe (two probes per wave, one word
+// Which kernel family serves a shape.  One wavefront per probe: packed words per lane (1, 2, 4, 8),
+// 0 = not served.  Half a wavefront per probe (two probes per wave, one word
 // per lane): yes or no.
 int wave_words_per_lane(int C, int L);
 bool half_wave_serves(int C, int L);

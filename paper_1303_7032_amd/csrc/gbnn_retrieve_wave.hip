@@ -574,7 +574,7 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
 
 // NW = packed words per lane, RULE = gbnn_rule, LG = log2(words per cluster).
 // Register budget, waves per SIMD: sum-of-max and hybrid 8 / 8 / 5 / 2 at 1 / 2 / 4 / 8 words per lane,
-// sum-of-sum 8 / 5 / 4 (not built at 8: its counters do not fit the registers).
+// sum-of-sum 8 / 5 / 4 / 2 (at 8 its high counter digits also take all 64 KiB of a workgroup's LDS).
 template <int NW, int RULE, int LG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 8 : NW == 2 ? (RULE == GBNN_SUM_OF_SUM ? 5 : 8) : NW == 8 ? 2 : RULE == GBNN_SUM_OF_SUM ? 4 : 5))) void
 k_retrieve_wave(RetrieveArgs a)
@@ -855,7 +855,7 @@ hipError_t launch_one(const RetrieveArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-// Eight words per lane (n up to 16384): sum-of-max and hybrid only, clusters of 8 to 64 lanes.
+// Eight words per lane (n up to 16384): clusters of 8 to 64 lanes.
 template <int LG>
 hipError_t launch_one8(const RetrieveArgs &a, hipStream_t s)
 {
@@ -863,8 +863,9 @@ hipError_t launch_one8(const RetrieveArgs &a, hipStream_t s)
     const int64_t blocks = (a.K + wpb - 1) / wpb;
     if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(64 * wpb);
-    if (a.rule == GBNN_SUM_OF_SUM) return hipErrorInvalidValue;
-    if (a.rule == GBNN_SUM_OF_MAX)
+    if (a.rule == GBNN_SUM_OF_SUM)
+        hipLaunchKernelGGL((k_retrieve_wave<8, GBNN_SUM_OF_SUM, LG>), grid, block, 0, s, a);
+    else if (a.rule == GBNN_SUM_OF_MAX)
         hipLaunchKernelGGL((k_retrieve_wave<8, GBNN_SUM_OF_MAX, LG>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((k_retrieve_wave<8, GBNN_HYBRID, LG>), grid, block, 0, s, a);

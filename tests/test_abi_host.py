@@ -152,7 +152,7 @@ def test_strerror_and_path(lib):
     assert gb.gbnn_retrieve_path(4, 16, "sum_of_max") == "generic"
     assert gb.gbnn_retrieve_path(16, 1024, "sum_of_max") == "wave8"
     assert gb.gbnn_retrieve_path(8, 2048, "hybrid") == "wave8"
-    assert gb.gbnn_retrieve_path(16, 1024, "sum_of_sum") == "generic"
+    assert gb.gbnn_retrieve_path(16, 1024, "sum_of_sum") == "wave8"
     assert gb.gbnn_retrieve_path(4, 4096, "sum_of_max") == "generic"
     assert gb.gbnn_retrieve_path(1, 16, "sum_of_max") == ""
 
