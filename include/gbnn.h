@@ -11,7 +11,7 @@
  *   - Every pointer is a DEVICE pointer owned by the caller (e.g. a torch tensor's data_ptr()).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
  *     work on that stream and return; they never allocate, free or synchronise, and the library
- *     keeps no state between calls.
+ *     keeps no state between calls (the one exception, for tests, is gbnn_set_kernel_choice).
  *   - Return value: GBNN_OK (0) or a negative gbnn_status.  All argument checks happen on the
  *     host before anything is enqueued; nothing is launched when an error is returned.
  *   - W layout ("canonical"): uint32_t[n][nw], nw = ceil(n/32), row-major; bit (j % 32) of word
@@ -192,6 +192,22 @@ const char *gbnn_strerror(int code);
  * rounded up (the extra neurons are never part of a message): retrieval then returns the same symbols,
  * and pass counts that can be larger by the pass that switches the extra neurons off. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
+
+/*
+ * For tests and A/B timing only: which kernel serves the calls that follow, in place of the library's own
+ * choice.  Process-wide and not synchronised with calls running on other threads; both start as
+ * "the library chooses".  Results are identical whatever is chosen: the kernels differ in speed only.
+ *   retrieve_family  GBNN_FAMILY_AUTO; GBNN_FAMILY_GENERIC = the any-shape kernel for every shape;
+ *                    GBNN_FAMILY_WAVE = one wavefront per probe also where two probes per wavefront
+ *                    would be chosen (shapes no register kernel serves still take the any-shape kernel)
+ *   store_kernel     GBNN_STORE_AUTO; GBNN_STORE_ATOMIC = one atomic OR per bit; GBNN_STORE_ROWS = rows
+ *                    built in LDS
+ * Returns GBNN_ERR_RULE for a value outside these enumerations (nothing is changed then).
+ * gbnn_retrieve_path reports the choice in force.
+ */
+enum { GBNN_FAMILY_AUTO = 0, GBNN_FAMILY_GENERIC = 1, GBNN_FAMILY_WAVE = 2 };
+enum { GBNN_STORE_AUTO = 0, GBNN_STORE_ATOMIC = 1, GBNN_STORE_ROWS = 2 };
+int gbnn_set_kernel_choice(int retrieve_family, int store_kernel);
 
 #ifdef __cplusplus
 }

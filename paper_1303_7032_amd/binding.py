@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_strerror.argtypes = [ci]
         L.gbnn_retrieve_path.restype = ctypes.c_char_p
         L.gbnn_retrieve_path.argtypes = [ci, ci, ci, vp, vp]
+        L.gbnn_set_kernel_choice.restype = ci
+        L.gbnn_set_kernel_choice.argtypes = [ci, ci]
         _lib = L
     return _lib
 
@@ -234,6 +236,17 @@ def gbnn_retrieve_path(C: int, L: int, rule, V0: torch.Tensor | None = None, V_o
     p = lib().gbnn_retrieve_path(C, L, _rule(rule), V0.data_ptr() if V0 is not None else 0,
                                  V_out.data_ptr() if V_out is not None else 0)
     return p.decode() if p else ""
+
+
+FAMILIES = {"auto": 0, "generic": 1, "wave": 2}
+STORE_KERNELS = {"auto": 0, "atomic": 1, "rows": 2}
+
+
+def gbnn_set_kernel_choice(retrieve_family="auto", store_kernel="auto") -> None:
+    """Tests and A/B timing: the kernel that serves the following calls (process-wide; "auto" = the library's choice)."""
+    f = FAMILIES[retrieve_family] if isinstance(retrieve_family, str) else int(retrieve_family)
+    k = STORE_KERNELS[store_kernel] if isinstance(store_kernel, str) else int(store_kernel)
+    _check(lib().gbnn_set_kernel_choice(f, k))
 
 
 def gbnn_sparse_bytes(C: int, L: int, nnz: int) -> int:

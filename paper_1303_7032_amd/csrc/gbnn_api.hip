@@ -1,6 +1,5 @@
 // Host side of the C ABI declared in include/gbnn.h: argument checks and kernel dispatch.
-#include <cstdlib>
-#include <cstring>
+#include <atomic>
 
 #include "gbnn_internal.h"
 
@@ -19,19 +18,19 @@ bool rule_ok(int rule) { return rule == GBNN_SUM_OF_SUM || rule == GBNN_SUM_OF_M
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
+// What gbnn_set_kernel_choice last set (tests and A/B timing); both start as "the library chooses".
+std::atomic<int> g_retrieve_family{GBNN_FAMILY_AUTO};
+std::atomic<int> g_store_kernel{GBNN_STORE_AUTO};
+
 // Kernel family for a call: 0 = any-shape kernel; 1, 2, 4, 8 = one wavefront per probe with that many packed
-// words per lane; kHalfPath = half a wavefront per probe.  The environment variables GBNN_FORCE_GENERIC=1
-// and GBNN_FORCE_WAVE=1 (no half-wave kernel) exist for tests and A/B timing.
+// words per lane; kHalfPath = half a wavefront per probe.
 constexpr int kHalfPath = 10;
 int pick_path(int C, int L, int rule, const void *V0, const void *Vout)
 {
-    const char *force = std::getenv("GBNN_FORCE_GENERIC");
-    if (force && force[0] == '1') return 0;
+    const int family = g_retrieve_family.load(std::memory_order_relaxed);
+    if (family == GBNN_FAMILY_GENERIC) return 0;
     if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;  // (the message boundary passes nullptr: no constraint)
-    const char *wave = std::getenv("GBNN_FORCE_WAVE");
-    if (!(wave && wave[0] == '1')) {
-        if (half_wave_serves(C, L)) return kHalfPath;
-    }
+    if (family != GBNN_FAMILY_WAVE && half_wave_serves(C, L)) return kHalfPath;
     (void)rule;
     return wave_words_per_lane(C, L);
 }
@@ -90,11 +89,8 @@ int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_
 {
     if (!shape_ok(C, L) || M < 0) return GBNN_ERR_SHAPE;
     if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
-    int path = kStoreAuto;  // GBNN_STORE_PATH=atomic|rows forces one of the two kernels (tests)
-    if (const char *p = std::getenv("GBNN_STORE_PATH")) {
-        if (std::strcmp(p, "atomic") == 0) path = kStoreAtomic;
-        if (std::strcmp(p, "rows") == 0) path = kStoreRows;
-    }
+    const int choice = g_store_kernel.load(std::memory_order_relaxed);
+    const int path = choice == GBNN_STORE_ATOMIC ? kStoreAtomic : choice == GBNN_STORE_ROWS ? kStoreRows : kStoreAuto;
     const hipError_t e = launch_store(W, C, L, (int)gbnn_w_row_words(C, L), msgs, M, status, path,
                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
@@ -200,6 +196,15 @@ int gbnn_retrieve_sparse(const void *Wp, size_t Wp_bytes, int C, int L, const in
                                                 (int)gbnn_w_row_words(C, L), probes, K, max_iters, bits_out,
                                                 symbols_out, iters_out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
+}
+
+int gbnn_set_kernel_choice(int retrieve_family, int store_kernel)
+{
+    if (retrieve_family < GBNN_FAMILY_AUTO || retrieve_family > GBNN_FAMILY_WAVE) return GBNN_ERR_RULE;
+    if (store_kernel < GBNN_STORE_AUTO || store_kernel > GBNN_STORE_ROWS) return GBNN_ERR_RULE;
+    g_retrieve_family.store(retrieve_family, std::memory_order_relaxed);
+    g_store_kernel.store(store_kernel, std::memory_order_relaxed);
+    return GBNN_OK;
 }
 
 const char *gbnn_strerror(int code)

@@ -3,8 +3,6 @@
 Everything here is integer / bit work, so the bar is exact equality: the packed W, every byte
 of every final activity vector, every entry of iters_out, and the retrieval error rate.
 """
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -26,11 +24,25 @@ def _need_gpu():
 
 
 @pytest.fixture(params=["auto", "atomic", "rows"])
-def store_path(request, monkeypatch):
+def store_path(request):
     """Both storing kernels (one atomic OR per bit; rows built in LDS), and the library's own choice."""
-    if request.param != "auto":
-        monkeypatch.setenv("GBNN_STORE_PATH", request.param)
-    return request.param
+    gb.gbnn_set_kernel_choice("auto", request.param)
+    yield request.param
+    gb.gbnn_set_kernel_choice("auto", "auto")
+
+
+class family:
+    """The kernel family the library picks, or the any-shape kernel for every shape, or one wavefront per
+    probe also where two probes per wavefront would be picked (gbnn_set_kernel_choice around the calls)."""
+
+    def __init__(self, force_generic=False, force_wave=False):
+        self.name = "generic" if force_generic else "wave" if force_wave else "auto"
+
+    def __enter__(self):
+        gb.gbnn_set_kernel_choice(self.name, "auto")
+
+    def __exit__(self, *exc):
+        gb.gbnn_set_kernel_choice("auto", "auto")
 
 
 def dev_store(C, L, msgs):
@@ -42,20 +54,11 @@ def dev_store(C, L, msgs):
 
 def dev_retrieve(W, C, L, V0, rule, gamma, cap, force_generic=False, force_wave=False, **kw):
     """gbnn_retrieve on the kernel family the library picks, or with the any-shape kernel forced, or
-    with the two-probes-per-wave kernel switched off (the library reads the environment per call)."""
-    want = {"GBNN_FORCE_GENERIC": "1" if force_generic else "0", "GBNN_FORCE_WAVE": "1" if force_wave else "0"}
-    old = {k: os.environ.get(k) for k in want}
-    os.environ.update(want)
-    try:
+    with the two-probes-per-wave kernel switched off."""
+    with family(force_generic, force_wave):
         V0d = torch.from_numpy(V0).cuda() if isinstance(V0, np.ndarray) else V0
         out, it = gb.gbnn_retrieve(W, C, L, V0d, rule, gamma, cap, **kw)
         torch.cuda.synchronize()
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
     return out.cpu().numpy(), it.cpu().numpy()
 
 
@@ -148,7 +151,7 @@ SHAPES = [
     (12, 256, 20000, 6, 300),  # 96 words: two words per lane, second slot half empty
     (16, 512, 100000, 8, 260),  # cfg5 shape: four words per lane
     (2, 2048, 3000, 1, 70),  # a cluster is a whole wave
-    (16, 1024, 60000, 8, 20),  # n = 16384, the largest: eight words per lane (sum-of-sum: any-shape kernel)
+    (16, 1024, 60000, 8, 20),  # n = 16384, the largest: eight words per lane
     (8, 2048, 40000, 4, 40),   # ... a cluster is a whole slot
     (64, 256, 8000, 32, 36),   # ... eight lanes per cluster
     (9, 1024, 30000, 4, 33),   # 288 words: the fifth slot half empty
@@ -199,18 +202,9 @@ def test_probes_from_stored_messages(networks, C, L, M, e, K, rule):
 
 
 def dev_retrieve_symbols(W, C, L, probes, rule, gamma, cap, force_generic=False, force_wave=False, **kw):
-    want = {"GBNN_FORCE_GENERIC": "1" if force_generic else "0", "GBNN_FORCE_WAVE": "1" if force_wave else "0"}
-    old = {k: os.environ.get(k) for k in want}
-    os.environ.update(want)
-    try:
+    with family(force_generic, force_wave):
         bits, sym, it = gb.gbnn_retrieve_symbols(W, C, L, torch.from_numpy(probes).cuda(), rule, gamma, cap, **kw)
         torch.cuda.synchronize()
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
     return [None if t is None else t.cpu().numpy() for t in (bits, sym, it)]
 
 
@@ -263,7 +257,10 @@ def test_messages_at_the_boundary_edge_cases(networks):
 
 
 @pytest.mark.parametrize("C,L,M", [(4, 16, 50), (5, 12, 200), (8, 32, 300), (8, 128, 5000), (8, 256, 20000),
-                                    (16, 512, 100000), (32, 32, 700), (2, 512, 30000), (12, 256, 20000)])
+                                    (16, 512, 100000), (32, 32, 700), (2, 512, 30000), (12, 256, 20000),
+                                    # eight words per lane: sum-of-sum digits beyond the registers, the hybrid's
+                                    # signal counter and the crowded-cluster walk at that width
+                                    (16, 1024, 60000), (8, 2048, 40000), (64, 256, 8000), (9, 1024, 30000)])
 @pytest.mark.parametrize("rule", RULES)
 def test_arbitrary_binary_probes(networks, C, L, M, rule):
     """Probes outside the one-active-neuron-per-cluster contract: several active neurons in a

@@ -12,7 +12,7 @@ from paper_1303_7032_amd import inputs
 pytestmark = pytest.mark.gpu
 
 RULES = ("sum_of_sum", "sum_of_max", "hybrid")
-FAMILIES = ({}, {"GBNN_FORCE_WAVE": "1"}, {"GBNN_FORCE_GENERIC": "1"})
+FAMILIES = ("auto", "wave", "generic")
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -22,11 +22,11 @@ def _need_gpu():
 
 
 @pytest.mark.parametrize("seed", [101, 202, 303])
-def test_random_retrievals(seed, monkeypatch):
+def test_random_retrievals(seed):
     rng = np.random.default_rng(seed)
     for case in range(40):
-        L = int(rng.choice([4, 16, 32, 64, 128, 256, 512, 1024]))
-        cmax = min(64, 8192 // L) if L >= 32 else min(64, 2048 // L)
+        L = int(rng.choice([4, 16, 32, 64, 128, 256, 512, 1024, 2048]))
+        cmax = min(64, 16384 // L) if L >= 32 else min(64, 2048 // L)  # up to the interface's n = 16384
         C = int(rng.integers(2, max(3, cmax + 1)))
         dens = float(rng.choice([0.01, 0.1, 0.25, 0.4, 0.6]))
         M = min(200000, max(2, int(np.log(1 - dens) / np.log(1 - 1.0 / (L * L)))))
@@ -49,21 +49,22 @@ def test_random_retrievals(seed, monkeypatch):
             gamma, cap = int(rng.choice([0, 1, 2, 7])), int(rng.choice([1, 2, 3, 5, 20]))
             ref, itref, _ = orc.retrieve(Wo, C, L, V0, rule, gamma, cap)
             rbits, rsym = orc.decode(C, L, ref)
-            for env in FAMILIES:
-                with monkeypatch.context() as mp:
-                    for name, val in env.items():
-                        mp.setenv(name, val)
+            for fam in FAMILIES:
+                gb.gbnn_set_kernel_choice(fam, "auto")
+                try:
                     out, it = gb.gbnn_retrieve(W, C, L, V0d, rule, gamma, cap)
                     bits, sym, it2 = gb.gbnn_retrieve_symbols(W, C, L, pd, rule, gamma, cap)
                     torch.cuda.synchronize()
-                what = (rule, gamma, cap, env)
+                finally:
+                    gb.gbnn_set_kernel_choice("auto", "auto")
+                what = (rule, gamma, cap, fam)
                 assert (out.cpu().numpy() == ref).all() and (it.cpu().numpy() == itref).all(), what
                 assert (bits.cpu().numpy().view(np.uint32) == rbits).all() and (sym.cpu().numpy() == rsym).all(), what
                 assert (it2.cpu().numpy() == itref).all(), what
 
 
 @pytest.mark.parametrize("seed", [11, 22])
-def test_random_stores_updates_and_lists(seed, monkeypatch):
+def test_random_stores_updates_and_lists(seed):
     rng = np.random.default_rng(seed)
     for case in range(60):
         lists = rng.random() < 0.6                      # the sparse W' needs L to be a multiple of 32
@@ -88,14 +89,15 @@ def test_random_stores_updates_and_lists(seed, monkeypatch):
         ref = orc.pack_bits(Wo)
         md = torch.from_numpy(msgs).cuda()
         for path in ("auto", "atomic", "rows"):
-            with monkeypatch.context() as mp:
-                if path != "auto":
-                    mp.setenv("GBNN_STORE_PATH", path)
+            gb.gbnn_set_kernel_choice("auto", path)
+            try:
                 W = gb.new_network(C, L)
                 st = torch.zeros(1, dtype=torch.int32, device="cuda")
                 h = int(rng.integers(0, M + 1))
                 gb.gbnn_store(W, C, L, md[:h].contiguous(), st)
                 gb.gbnn_store(W, C, L, md[h // 2:].contiguous(), st)
+            finally:
+                gb.gbnn_set_kernel_choice("auto", "auto")
                 assert (W.cpu().numpy().view(np.uint32) == ref).all(), path
                 assert int(st.item()) == (1 if len(good) < M else 0), path
         W = gb.new_network(C, L)
