@@ -54,7 +54,8 @@ typedef enum {
     GBNN_ERR_GAMMA = -4,     /* gamma outside [0, GBNN_MAX_GAMMA] */
     GBNN_ERR_ITERS = -5,     /* max_iters < 1 */
     GBNN_ERR_WORKSPACE = -6, /* workspace NULL, misaligned (needs 256 bytes) or too small */
-    GBNN_ERR_DEVICE = -7     /* the HIP runtime refused a launch */
+    GBNN_ERR_DEVICE = -7,    /* the HIP runtime refused a launch */
+    GBNN_ERR_TOO_LARGE = -8  /* gbnn_retrieve_static: the network exceeds GBNN_STATIC_MAX_N neurons */
 } gbnn_status;
 
 /* Words per row of W: ceil(C*L/32).  0 if the shape is outside the limits. */
@@ -132,6 +133,24 @@ int gbnn_store_update(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M,
 int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
                   int gamma, int max_iters, int32_t *iters_out, void *workspace, size_t workspace_bytes,
                   void *stream);
+
+/*
+ * gbnn_retrieve for callers that cannot allocate device memory and so have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The table that
+ * gbnn_prepare derives from W is built, on every call, in a device array that is part of the library
+ * itself (about 8.1 MiB on every GPU the library runs on, held until the process ends), and the
+ * retrieval then reads it there: gbnn_prepare followed by gbnn_retrieve, enqueued on `stream`, same
+ * arguments, same results, and no allocation anywhere.
+ *   Limit: n = C*L <= GBNN_STATIC_MAX_N, else GBNN_ERR_TOO_LARGE (nothing is enqueued).
+ *   All calls on one GPU share that one array: calls that overlap in time on one GPU (different
+ *   streams or threads) race; order them on one stream.  The array keeps what the last call wrote;
+ *   every word a call reads is rewritten by that call first.
+ *   Because the table is rebuilt per call (a pass over W: 18 us at C=8, L=256), callers that can
+ *   hold a workspace should use gbnn_prepare once and gbnn_retrieve.
+ */
+#define GBNN_STATIC_MAX_N 8192
+int gbnn_retrieve_static(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
+                         int gamma, int max_iters, int32_t *iters_out, void *stream);
 
 /*
  * The same retrieval with messages at the boundary (Section II-A: a message is C symbols, a probe is

@@ -18,7 +18,8 @@ SUM_OF_SUM, SUM_OF_MAX, HYBRID = 0, 1, 2
 RULES = {"sum_of_sum": SUM_OF_SUM, "sum_of_max": SUM_OF_MAX, "hybrid": HYBRID}
 
 GBNN_OK = 0
-ERRORS = {"NULL": -1, "SHAPE": -2, "RULE": -3, "GAMMA": -4, "ITERS": -5, "WORKSPACE": -6, "DEVICE": -7}
+ERRORS = {"NULL": -1, "SHAPE": -2, "RULE": -3, "GAMMA": -4, "ITERS": -5, "WORKSPACE": -6, "DEVICE": -7,
+          "TOO_LARGE": -8}
 
 
 class GbnnError(RuntimeError):
@@ -51,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_store_update.argtypes = [vp, ci, ci, vp, i64, vp, vp, sz, vp]
         L.gbnn_retrieve.restype = ci
         L.gbnn_retrieve.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp, sz, vp]
+        L.gbnn_retrieve_static.restype = ci
+        L.gbnn_retrieve_static.argtypes = [vp, ci, ci, vp, vp, i64, ci, ci, ci, vp, vp]
         L.gbnn_retrieve_symbols.restype = ci
         L.gbnn_retrieve_symbols.argtypes = [vp, ci, ci, vp, i64, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         L.gbnn_sparse_bytes.restype = sz
@@ -191,6 +194,27 @@ def gbnn_retrieve(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma
                                gamma, max_iters, iters_out.data_ptr() if iters_out is not None else 0,
                                workspace.data_ptr(), workspace.numel(), _stream(V0)))
     return V_out, iters_out
+
+
+def gbnn_retrieve_static(W: torch.Tensor, C: int, L: int, V0: torch.Tensor, rule, gamma: int, max_iters: int,
+                         V_out: torch.Tensor, iters_out: torch.Tensor | None = None) -> None:
+    """gbnn_retrieve without a workspace (the library's own static device array holds the prepared table);
+    nothing is allocated here either: the caller passes every output."""
+    _dev(W, torch.int32, "W")
+    _dev(V0, torch.uint8, "V0")
+    _dev(V_out, torch.uint8, "V_out")
+    n = C * L
+    if W.numel() * 4 != gbnn_w_bytes(C, L) or V0.numel() % n or V_out.numel() != V0.numel():
+        _check(ERRORS["SHAPE"])
+    K = V0.numel() // n
+    it = 0
+    if iters_out is not None:
+        _dev(iters_out, torch.int32, "iters_out")
+        if iters_out.numel() != K:
+            _check(ERRORS["SHAPE"])
+        it = iters_out.data_ptr()
+    _check(lib().gbnn_retrieve_static(W.data_ptr(), C, L, V0.data_ptr() if K else 0, V_out.data_ptr() if K else 0, K,
+                                      _rule(rule), gamma, max_iters, it, _stream(V0)))
 
 
 SYM_NONE, SYM_AMBIGUOUS = -1, -2

@@ -5,7 +5,31 @@
 
 using namespace gbnn;
 
+// The prepared table of gbnn_retrieve_static: device memory of the library itself, one copy on every
+// GPU the library runs on, held until the process ends.  Room for the table of any network of up to
+// GBNN_STATIC_MAX_N neurons ((n + C + 2) rows of n/32 words, rounded up to 256 bytes, plus 256 for the
+// flags).  In host code this name only stands for the symbol; the array's address on a device comes
+// from hipGetSymbolAddress (static_scratch below).
+constexpr size_t kStaticScratchBytes =
+    ((size_t)(GBNN_STATIC_MAX_N + GBNN_MAX_C + 2) * (GBNN_STATIC_MAX_N / 32) * 4 + 255) / 256 * 256 + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Address of `scratch` on the current device, looked up once per device (with that device current).
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // (two threads racing here store the same address)
+    }
+    return p;
+}
 
 bool shape_ok(int C, int L)
 {
@@ -142,6 +166,25 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
     return retrieve_common(a, W, C, L, K, rule, gamma, max_iters, iters_out, workspace, workspace_bytes, stream);
 }
 
+int gbnn_retrieve_static(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V_out, int64_t K, int rule,
+                         int gamma, int max_iters, int32_t *iters_out, void *stream)
+{
+    if (!shape_ok(C, L) || K < 0 || K > GBNN_MAX_K) return GBNN_ERR_SHAPE;
+    if (!rule_ok(rule)) return GBNN_ERR_RULE;
+    if (gamma < 0 || gamma > GBNN_MAX_GAMMA) return GBNN_ERR_GAMMA;
+    if (max_iters < 1) return GBNN_ERR_ITERS;
+    if (!W || (K > 0 && (!V0 || !V_out))) return GBNN_ERR_NULL;
+    const int nw = (int)gbnn_w_row_words(C, L);
+    if (C * L > GBNN_STATIC_MAX_N || workspace_total_bytes(C, L, nw) > kStaticScratchBytes) return GBNN_ERR_TOO_LARGE;
+    if (K == 0) return GBNN_OK;
+    void *ws = static_scratch();
+    if (!ws) return GBNN_ERR_DEVICE;
+    // every word of the table that retrieval reads is rewritten here, so what the last call left does not matter
+    const int e = gbnn_prepare(W, C, L, ws, kStaticScratchBytes, stream);
+    if (e != GBNN_OK) return e;
+    return gbnn_retrieve(W, C, L, V0, V_out, K, rule, gamma, max_iters, iters_out, ws, kStaticScratchBytes, stream);
+}
+
 int gbnn_retrieve_symbols(const uint32_t *W, int C, int L, const int32_t *probes, int64_t K, int rule, int gamma,
                           int max_iters, uint32_t *bits_out, int32_t *symbols_out, int32_t *iters_out,
                           void *workspace, size_t workspace_bytes, void *stream)
@@ -218,6 +261,7 @@ const char *gbnn_strerror(int code)
     case GBNN_ERR_ITERS: return "max_iters must be at least 1";
     case GBNN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than gbnn_workspace_bytes";
     case GBNN_ERR_DEVICE: return "the HIP runtime refused a kernel launch";
+    case GBNN_ERR_TOO_LARGE: return "gbnn_retrieve_static serves networks of up to 8192 neurons";
     default: return "unknown status code";
     }
 }
