@@ -286,6 +286,68 @@ __device__ __forceinline__ void fetch_and_apply(const Ctx<NW> &x, uint32_t (&pw)
     for (int u = 0; u < NW; ++u) acc[u] &= R[u];
 }
 
+// acc &= the row of the active neuron of every nonzero word of v[], for v[] whose words hold at most one
+// bit each and whose clusters hold at most one active neuron each (the probe contract: one active neuron
+// per known cluster), so that "for every cluster the OR of its rows" is the AND of all rows.  The rows are
+// found without ranking or pushing: the nonzero lanes of a slot are a scalar mask, walked bit by bit, and
+// each lane's row offset is read out of the lane.  With one word per lane the offsets go straight into the
+// loads, four rows at a time (past the end the last row is repeated); with more words per lane they are
+// first collected in a list, lane i holding entry i, and fetched eight (four) at a time.
+template <int NW>
+__device__ __forceinline__ void and_single_rows(const Ctx<NW> &x, const uint32_t (&v)[NW], uint32_t (&acc)[NW])
+{
+    if constexpr (NW == 1) {
+        const uint32_t joff = __umul24(x.bit0[0] + (uint32_t)__builtin_ctz(v[0] | 0x80000000u), x.rowbytes);
+        uint64_t m = ballot(v[0] != 0u);
+        while (m) {
+            uint32_t so[4];
+            so[0] = readlane(joff, __builtin_ctzll(m));
+            m &= m - 1ull;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) {
+                so[q] = so[q - 1];
+                if (m) {
+                    so[q] = readlane(joff, __builtin_ctzll(m));
+                    m &= m - 1ull;
+                }
+            }
+            if (acc[0] != 0u) {  // a lane with nothing left on does not need its word of the rows
+                uint32_t r[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) r[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, x.woffb[0], so[q], 0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[0] &= r[q];
+            }
+        }
+    } else {
+        uint32_t offv = 0u, last = 0u;
+        int total = 0;
+#pragma unroll
+        for (int t = 0; t < NW; ++t) {
+            const uint32_t joff = __umul24(x.bit0[t] + (uint32_t)__builtin_ctz(v[t] | 0x80000000u), x.rowbytes);
+            uint64_t m = ballot(v[t] != 0u);
+            while (m && total < 64) {
+                last = readlane(joff, __builtin_ctzll(m));
+                m &= m - 1ull;
+                offv = x.lane == total ? last : offv;
+                ++total;
+            }
+        }
+        if (total == 0) return;
+        offv = x.lane < total ? offv : last;  // lanes past the end repeat the last entry: whole batches can be fetched
+        int i0 = 0;
+        while (i0 < total) {
+            if (total - i0 > 4) {
+                and_batch<NW, 8>(x, offv, i0, acc);
+                i0 += 8;
+            } else {
+                and_batch<NW, 4>(x, offv, i0, acc);
+                i0 += 4;
+            }
+        }
+    }
+}
+
 // The same update as fetch_and_apply for crowded clusters (dense networks: tens of active neurons per
 // cluster, most lanes of a cluster holding some), without building a list: cluster by cluster, every
 // lane of the cluster offers the row of its lowest remaining bit (a lane with none offers the all-zero
@@ -487,6 +549,28 @@ __device__ __forceinline__ void signals_equal(const Ctx<NW> &x, const uint32_t (
     }
 }
 
+// Bit q of the result = bit `bitpos` of the word at byte offset `woff` of the row at byte offset
+// readlane(offv, i0 + q), q < B: B single-word loads in flight together (i0 + B <= 64).  Only the lanes with
+// `take` set load (the others return 0): the address unit works through a load 16 lanes at a time and skips
+// idle ones.  (The row offsets are read out of the lanes before the lanes are masked.)
+template <int B, int NW>
+__device__ __forceinline__ uint32_t gather_bits(const Ctx<NW> &x, uint32_t woff, uint32_t offv, int i0, uint32_t bitpos,
+                                                bool take)
+{
+    uint32_t so[B];
+#pragma unroll
+    for (int q = 0; q < B; ++q) so[q] = readlane(offv, i0 + q);
+    uint32_t t = 0u;
+    if (take) {
+        uint32_t w[B];
+#pragma unroll
+        for (int q = 0; q < B; ++q) w[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, woff, so[q], 0);
+#pragma unroll
+        for (int q = 0; q < B; ++q) t |= ((w[q] >> bitpos) & 1u) << q;
+    }
+    return t;
+}
+
 // The passes after the first on the adjacency matrix of the candidates (sum-of-max and hybrid).
 //
 // Setting: every known cluster of the probe holds one active neuron, all of them survived pass 1 (so
@@ -522,16 +606,23 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
     const uint32_t bitpos = jq & 31u;
     const uint32_t offv = __umul24(jq, x.rowbytes);
 
-    // A: lane q reads, from the row of every candidate q', the one word that holds its own bit
-    uint32_t A = 0u;
-    for (int i0 = 0; i0 < T; i0 += 4) {
-        uint32_t w[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) w[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, woff, readlane(offv, i0 + q), 0);
-        uint32_t t = 0u;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) t |= ((w[q] >> bitpos) & 1u) << q;
-        A |= t << i0;
+    // A: lane q reads, from the row of every candidate q', the one word that holds its own bit.  All
+    // loads are issued before the first is waited for (a probe's time is its chain of memory round trips),
+    // in a batch of 8, 16, 24 or 32; positions past T repeat the last candidate.  Only the lanes that hold
+    // a candidate take part: the address unit works through a load 16 lanes at a time and skips idle ones.
+    uint32_t A;
+    if (NW > 1) {
+        // (more words per lane: the networks whose table exceeds an L2; four at a time measured best there)
+        A = 0u;
+        for (int i0 = 0; i0 < T; i0 += 4) A |= gather_bits<4>(x, woff, offv, i0, bitpos, true) << i0;
+    } else if (T <= 8) {
+        A = gather_bits<8>(x, woff, offv, 0, bitpos, inl);
+    } else if (T <= 16) {
+        A = gather_bits<16>(x, woff, offv, 0, bitpos, inl);
+    } else if (T <= 24) {
+        A = gather_bits<24>(x, woff, offv, 0, bitpos, inl);
+    } else {
+        A = gather_bits<32>(x, woff, offv, 0, bitpos, inl);
     }
 
     uint32_t m = maskT;          // candidates still on
@@ -626,11 +717,19 @@ k_retrieve_wave(RetrieveArgs a)
         if (RULE == GBNN_SUM_OF_MAX || RULE == GBNN_HYBRID) {
             // Erased clusters = clusters with no active neuron in the probe.
             bool erased[NW];
-#pragma unroll
-            for (int t = 0; t < NW; ++t) erased[t] = x.valid[t] && group_or<LG>(v[t]) == 0u;
             uint32_t acc[NW], d[NW], probe[NW];
+            // The probe contract: every known cluster holds exactly one active neuron.
+            int known = 0, nzlanes = 0;
+            uint64_t multi = 0;
 #pragma unroll
-            for (int t = 0; t < NW; ++t) probe[t] = v[t];
+            for (int t = 0; t < NW; ++t) {
+                erased[t] = x.valid[t] && group_or<LG>(v[t]) == 0u;
+                probe[t] = v[t];
+                known += __builtin_popcountll(ballot(x.islead[t] && !erased[t]));
+                nzlanes += __builtin_popcountll(ballot(v[t] != 0u));
+                multi |= ballot((v[t] & (v[t] - 1u)) != 0u);
+            }
+            const bool contract = !multi && nzlanes == known;
             int p = 1;
             bool changed = true;
             if (RULE == GBNN_SUM_OF_MAX) {
@@ -638,41 +737,32 @@ k_retrieve_wave(RetrieveArgs a)
                 // contribute the rows of their active neurons, the (fully active) erased clusters
                 // their summary rows.
                 uint32_t pw[NW];
-                uint64_t summask[NW];
+                uint64_t summask[NW], anysum = 0;
                 const uint64_t full = *a.full;
 #pragma unroll
                 for (int t = 0; t < NW; ++t) {
                     pw[t] = v[t];
                     // (a summary row that is all ones changes nothing: not fetched)
                     summask[t] = ballot(erased[t] && x.islead[t] && !((full >> (x.myc[t] & 63u)) & 1ull));
+                    anysum |= summask[t];
                     if (erased[t]) v[t] = 0xFFFFFFFFu;
                     acc[t] = v[t];
                 }
-                fetch_and_apply<NW, LG>(x, pw, summask, acc);
+                if (contract && !anysum)
+                    and_single_rows<NW>(x, pw, acc);  // no summary row to fetch: the AND of the known neurons' rows
+                else
+                    fetch_and_apply<NW, LG>(x, pw, summask, acc);
                 changed = diff(acc, v, d);
             } else {
                 // Algorithm 2, lines 1-5.
-                int known = 0, nzlanes = 0;
-                uint64_t multi = 0;
+                if (contract) {
+                    // Every known cluster holds exactly one active neuron.  Then "exactly C - e signals"
+                    // means "adjacent to every known active neuron": the AND of their rows over the erased
+                    // clusters.
 #pragma unroll
-                for (int t = 0; t < NW; ++t) {
-                    known += __builtin_popcountll(ballot(x.islead[t] && !erased[t]));
-                    nzlanes += __builtin_popcountll(ballot(v[t] != 0u));
-                    multi |= ballot((v[t] & (v[t] - 1u)) != 0u);
-                }
-                if (!multi && nzlanes == known) {
-                    // Every known cluster holds exactly one active neuron (the probe contract).  Then
-                    // "exactly C - e signals" means "adjacent to every known active neuron": the AND of
-                    // their rows over the erased clusters.
-                    uint32_t pw[NW];
-                    uint64_t summask[NW];
-#pragma unroll
-                    for (int t = 0; t < NW; ++t) {
+                    for (int t = 0; t < NW; ++t)
                         acc[t] = erased[t] ? 0xFFFFFFFFu : 0u;  // (known clusters are restored below: their lanes fetch nothing)
-                        pw[t] = v[t];
-                        summask[t] = 0;
-                    }
-                    fetch_and_apply<NW, LG>(x, pw, summask, acc);
+                    and_single_rows<NW>(x, v, acc);
 #pragma unroll
                     for (int t = 0; t < NW; ++t) {
                         acc[t] = erased[t] ? acc[t] : v[t];
@@ -694,20 +784,16 @@ k_retrieve_wave(RetrieveArgs a)
             // in every erased cluster) finishes on the candidates' adjacency matrix; any other probe, and
             // a probe whose pass 1 changed nothing, takes the general loop below.
             bool finished = false;
-            if (changed) {
-                uint64_t multi = 0, lost = 0, bare = 0;
-                int nz = 0, known = 0;
+            if (changed && contract) {
+                uint64_t lost = 0, bare = 0;
                 uint32_t pw[NW];
                 uint64_t summask[NW];
 #pragma unroll
                 for (int t = 0; t < NW; ++t) {
-                    nz += __builtin_popcountll(ballot(probe[t] != 0u));
-                    multi |= ballot((probe[t] & (probe[t] - 1u)) != 0u);
                     lost |= ballot(!erased[t] && acc[t] != probe[t]);
                     pw[t] = erased[t] ? acc[t] : 0u;
                     bare |= ballot(erased[t] && group_or<LG>(pw[t]) == 0u);
                     summask[t] = 0;
-                    known += __builtin_popcountll(ballot(x.islead[t] && !erased[t]));
                 }
                 // a cheap lower bound of the number of candidates: lanes with one, plus lanes with two or more
                 int atleast = 0;
@@ -715,7 +801,7 @@ k_retrieve_wave(RetrieveArgs a)
                 for (int t = 0; t < NW; ++t)
                     atleast += __builtin_popcountll(ballot(pw[t] != 0u)) +
                                __builtin_popcountll(ballot((pw[t] & (pw[t] - 1u)) != 0u));
-                if (!multi && !lost && !bare && nz == known && atleast <= 32) {
+                if (!lost && !bare && atleast <= 32) {
                     uint32_t list;
                     uint32_t cand[NW], first_rank[NW];
 #pragma unroll
