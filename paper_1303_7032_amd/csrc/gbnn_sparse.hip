@@ -8,18 +8,20 @@
 //   cols     uint16[...]     neuron numbers, ascending within a list; to the end of the buffer
 // Retrieval: one wavefront per probe.  The activity vector lives in registers (word w in lane w % 64);
 // a pass walks the clusters whose active set changed in the pass before (Lemma 1: the others cannot
-// switch anything off).  A fully active cluster contributes its summary row; any other cluster c has the
-// neighbour lists of its active neurons scattered into a bit vector T in LDS (one lane per list entry,
-// ds_or), and every neuron outside c that is not in T goes off.  The state and the number of passes are
-// those of the kernels that read the packed W.
+// switch anything off).  A fully active cluster contributes its summary row.  The active neurons of the
+// other clusters to walk are listed in LDS, and their neighbour lists are walked side by side: the 64
+// lanes are split evenly among up to 64 listed neurons (64 lanes on one list, 32 on each of two, ... one
+// lane per list), every lane reads eight list entries per load and ORs them into the bit vector T of the
+// neuron's cluster in LDS (ds_or); then every neuron outside a walked cluster that is not in that
+// cluster's T goes off.  A pass is thus a fixed, short chain of memory round trips (offsets, list chunks)
+// whatever the number of active neurons.  The state and the number of passes are those of the kernels that
+// read the packed W.
 #include "gbnn_device.h"
 #include "gbnn_internal.h"
 
 namespace gbnn {
 namespace {
 
-constexpr int kSparseMaxWords = GBNN_MAX_N / 32;       // packed words of an activity vector, at most
-constexpr int kSparseSlots = kSparseMaxWords / 64;     // ... per lane
 constexpr int kSparseWaves = 4;                        // probes per workgroup
 
 // LDS traffic between the lanes of one wave: make earlier writes visible to later reads.
@@ -143,28 +145,39 @@ struct SparseArgs {
     int32_t *sym_out;
     int32_t *iters;
     int64_t K;
-    int C, L, nw, wpc;  // wpc = L / 32 words per cluster
+    int C, L, n, nw, wpc;  // wpc = L / 32 words per cluster
+    int group;             // clusters whose bit vectors T fit a wave's LDS at once
+    int wave_words;        // LDS words per wave
     int max_iters;
 };
 
+constexpr int kSparseList = 128;  // neurons listed at a time
+
+// LDS of one wave: cur[nw] (the activity vector, for the per-cluster statistics), nlist[kSparseList],
+// T[group][nw].
+__host__ __device__ inline int sparse_wave_words(int nw, int group) { return nw + kSparseList + group * nw; }
+
+// NS = words of the activity vector per lane (1, 2, 4 or 8: nw <= 64 NS).
+template <int NS>
 __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArgs a)
 {
-    __shared__ uint32_t lds[kSparseWaves][2][kSparseMaxWords];
+    extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int64_t k = (int64_t)blockIdx.x * kSparseWaves + wave;
     if (k >= a.K) return;  // the whole wave
-    uint32_t *cur = lds[wave][0];
-    uint32_t *T = lds[wave][1];
     const int nw = a.nw, wpc = a.wpc, C = a.C, L = a.L;
+    uint32_t *cur = lds + wave * a.wave_words;
+    uint32_t *nlist = cur + nw;
+    uint32_t *T = nlist + kSparseList;
     const uint64_t summary_full = *a.full;
 
     // word w = lane + 64 u of the activity vector; its cluster; Section III-C: an erased cluster starts
     // with all of its neurons on, a known one with the neuron of its symbol
-    uint32_t v[kSparseSlots], d[kSparseSlots], acc[kSparseSlots];
-    int cl[kSparseSlots];
+    uint32_t v[NS], d[NS], acc[NS];
+    int cl[NS];
 #pragma unroll
-    for (int u = 0; u < kSparseSlots; ++u) {
+    for (int u = 0; u < NS; ++u) {
         const int w = lane + 64 * u;
         cl[u] = w < nw ? w / wpc : -1;
         v[u] = 0u;
@@ -180,7 +193,7 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
     for (int p = 1;; ++p) {
         // per cluster: number of active neurons, and whether any changed in the pass before
 #pragma unroll
-        for (int u = 0; u < kSparseSlots; ++u) {
+        for (int u = 0; u < NS; ++u) {
             const int w = lane + 64 * u;
             if (w < nw) {
                 cur[w] = v[u];
@@ -200,68 +213,115 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
         uint64_t srcm = p == 1 ? ballot(lane < C) : ballot(lane < C && chg != 0u);
         wave_lds_sync();
 #pragma unroll
-        for (int u = 0; u < kSparseSlots; ++u) acc[u] = emptym ? 0u : v[u];
+        for (int u = 0; u < NS; ++u) acc[u] = emptym ? 0u : v[u];
         if (emptym) srcm = 0;  // a cluster without an active neuron: nobody reaches C - 1 clusters
-        while (srcm) {
-            const int c = __builtin_ctzll(srcm);
-            srcm &= srcm - 1ull;
-            if ((fullm >> c) & 1ull) {
-                if (!((summary_full >> c) & 1ull)) {
+        // fully active clusters: their summary rows (one that is all ones changes nothing)
+        for (uint64_t fm = srcm & fullm & ~summary_full; fm; fm &= fm - 1ull) {
+            const int c = __builtin_ctzll(fm);
 #pragma unroll
-                    for (int u = 0; u < kSparseSlots; ++u) {
-                        const int w = lane + 64 * u;
-                        if (w < nw) acc[u] &= a.summary[(int64_t)c * nw + w];
-                    }
-                }
-                continue;
-            }
-#pragma unroll
-            for (int u = 0; u < kSparseSlots; ++u) {
+            for (int u = 0; u < NS; ++u) {
                 const int w = lane + 64 * u;
-                if (w < nw) T[w] = 0u;
+                if (w < nw) acc[u] &= a.summary[(int64_t)c * nw + w];
             }
-            wave_lds_sync();
-            for (int i0 = 0; i0 < wpc; i0 += 64) {
-                const uint32_t word = i0 + lane < wpc ? cur[c * wpc + i0 + lane] : 0u;
-                uint64_t holders = ballot(word != 0u);
-                while (holders) {
-                    const int l = __builtin_ctzll(holders);
-                    holders &= holders - 1ull;
-                    uint32_t bits = readlane(word, l);
-                    while (bits) {
-                        const int b = __builtin_ctz(bits);
-                        bits &= bits - 1u;
-                        const int j = c * L + (i0 + l) * 32 + b;
-                        const uint32_t beg = a.offsets[j];
+        }
+        // the other clusters to walk, as many at a time as have their bit vectors T in LDS together
+        uint64_t walk = srcm & ~fullm;
+        while (walk) {
+            uint64_t grp = 0;
+            for (int g = 0; g < a.group && walk; ++g) {
+                grp |= walk & (0ull - walk);
+                walk &= walk - 1ull;
+            }
+            const int ng = __builtin_popcountll(grp);
+            for (int i = lane; i < ng * nw; i += 64) T[i] = 0u;
+            // the active neurons of these clusters, and for each the row of T its list goes to
+            uint32_t pw[NS], trow[NS];
+#pragma unroll
+            for (int u = 0; u < NS; ++u) {
+                const bool in = cl[u] >= 0 && ((grp >> cl[u]) & 1ull);
+                pw[u] = in ? v[u] : 0u;
+                trow[u] = in ? (uint32_t)__builtin_popcountll(grp & ((1ull << cl[u]) - 1ull)) : 0u;
+            }
+            for (;;) {
+                // list up to kSparseList of them: entry = (row of T) << 16 | neuron.  The position of a lane's
+                // first bit = the bits in lower lanes = sum over r of #(lower lanes with more than r bits).
+                uint32_t base = 0;
+                bool left = false;
+#pragma unroll
+                for (int u = 0; u < NS; ++u) {
+                    const uint32_t pc = __popc(pw[u]);
+                    uint64_t mk = ballot(pc > 0u);
+                    if (!mk) continue;
+                    uint32_t pos = base;
+                    for (uint32_t r = 1; mk; ++r) {
+                        pos += mbcnt(mk);
+                        base += (uint32_t)__builtin_popcountll(mk);
+                        mk = ballot(pc > r);
+                    }
+                    while (pw[u] && pos < (uint32_t)kSparseList) {
+                        const int b = __builtin_ctz(pw[u]);
+                        pw[u] &= pw[u] - 1u;
+                        nlist[pos++] = (trow[u] << 16) | (uint32_t)((lane + 64 * u) * 32 + b);
+                    }
+                    left = left || pw[u] != 0u;
+                }
+                const int listed = base < (uint32_t)kSparseList ? (int)base : kSparseList;
+                wave_lds_sync();
+                // walk the lists, up to 64 neurons side by side, P lanes on each
+                for (int n0 = 0; n0 < listed; n0 += 64) {
+                    const int here = listed - n0 < 64 ? listed - n0 : 64;
+                    int lgp = 6;  // P = 2^lgp lanes per list: 64 for one neuron, 32 for two, ..., 1 for 33 to 64
+                    while ((here << lgp) > 64) --lgp;
+                    const int ni = lane >> lgp, sub = lane & ((1 << lgp) - 1);
+                    if (ni < here) {
+                        const uint32_t ent = nlist[n0 + ni];
+                        const uint32_t j = ent & 0xFFFFu;
+                        uint32_t *Tr = T + (ent >> 16) * nw;
                         uint32_t end = a.offsets[j + 1];
                         end = end < a.capacity ? end : a.capacity;
-                        // four loads in flight per lane before the first of them is needed
-                        // (entry numbers stay far below 2^32: at most n * n of them)
-                        for (uint32_t t0 = beg; t0 < end; t0 += 256) {
-                            uint32_t col[4];
+                        uint32_t beg = a.offsets[j];
+                        beg = beg < end ? beg : end;
+                        // aligned chunks of eight entries; two loads in flight per lane
+                        const uint32_t step = 8u << lgp;
+                        for (uint32_t t0 = (beg & ~7u) + 8u * (uint32_t)sub; t0 < end; t0 += 2u * step) {
+                            uint4 ch[2];
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                const uint32_t t = t0 + 64u * q + lane;
-                                col[q] = t < end ? (uint32_t)a.cols[t] : 0xFFFFFFFFu;
+                            for (int q = 0; q < 2; ++q) {
+                                const uint32_t t = t0 + q * step;
+                                ch[q] = t < end ? *reinterpret_cast<const uint4 *>(a.cols + t) : make_uint4(0, 0, 0, 0);
                             }
 #pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                if (col[q] != 0xFFFFFFFFu) atomicOr(&T[col[q] >> 5], 1u << (col[q] & 31));
+                            for (int q = 0; q < 2; ++q) {
+                                const uint32_t t = t0 + q * step;
+                                const uint32_t wd[4] = {ch[q].x, ch[q].y, ch[q].z, ch[q].w};
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) {
+                                    const uint32_t col = (wd[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                                    const uint32_t idx = t + (uint32_t)e;
+                                    if (idx >= beg && idx < end && col < (uint32_t)a.n) atomicOr(&Tr[col >> 5], 1u << (col & 31u));
+                                }
+                            }
                         }
                     }
                 }
+                wave_lds_sync();
+                if (!ballot(left)) break;
             }
-            wave_lds_sync();
+            // every neuron outside a walked cluster that is not in that cluster's T goes off
+            int row = 0;
+            for (uint64_t g = grp; g; g &= g - 1ull, ++row) {
+                const int c = __builtin_ctzll(g);
 #pragma unroll
-            for (int u = 0; u < kSparseSlots; ++u) {
-                const int w = lane + 64 * u;
-                if (w < nw && cl[u] != c) acc[u] &= T[w];
+                for (int u = 0; u < NS; ++u) {
+                    const int w = lane + 64 * u;
+                    if (w < nw && cl[u] != c) acc[u] &= T[row * nw + w];
+                }
             }
             wave_lds_sync();
         }
         bool changed = false;
 #pragma unroll
-        for (int u = 0; u < kSparseSlots; ++u) {
+        for (int u = 0; u < NS; ++u) {
             d[u] = acc[u] ^ v[u];
             changed = changed || d[u] != 0u;
             v[u] = acc[u];
@@ -280,14 +340,14 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
     if (a.iters && lane == 0) a.iters[k] = iters;
     if (a.bits_out) {
 #pragma unroll
-        for (int u = 0; u < kSparseSlots; ++u) {
+        for (int u = 0; u < NS; ++u) {
             const int w = lane + 64 * u;
             if (w < nw) a.bits_out[k * nw + w] = v[u];
         }
     }
     if (a.sym_out) {
 #pragma unroll
-        for (int u = 0; u < kSparseSlots; ++u) {
+        for (int u = 0; u < NS; ++u) {
             const int w = lane + 64 * u;
             if (w < nw) cur[w] = v[u];
         }
@@ -314,6 +374,14 @@ size_t sparse_full_offset(int C, int n, int nw)
 }
 size_t sparse_cols_offset(int C, int n, int nw) { return sparse_full_offset(C, n, nw) + 256; }
 
+// Entries of cols[] a buffer of Wp_bytes has room for: whole 16-byte pieces only (retrieval reads the lists
+// eight entries at a time), the same figure for filling and for reading.
+static uint32_t sparse_capacity(size_t Wp_bytes, int C, int n, int nw)
+{
+    const size_t room = ((Wp_bytes - sparse_cols_offset(C, n, nw)) & ~(size_t)15) / sizeof(uint16_t);
+    return room > 0xFFFFFFF8ull ? 0xFFFFFFF8u : (uint32_t)room;
+}
+
 hipError_t launch_sparse_count(const uint32_t *W, int n, int nw, unsigned long long *total, hipStream_t s)
 {
     hipLaunchKernelGGL(k_sparse_zero, dim3(1), dim3(64), 0, s, total);
@@ -334,8 +402,7 @@ hipError_t launch_sparsify(const uint32_t *W, int C, int L, int nw, char *Wp, si
     uint32_t *summary = reinterpret_cast<uint32_t *>(Wp + sparse_summary_offset(n));
     uint64_t *full = reinterpret_cast<uint64_t *>(Wp + sparse_full_offset(C, n, nw));
     uint16_t *cols = reinterpret_cast<uint16_t *>(Wp + sparse_cols_offset(C, n, nw));
-    const size_t room = (Wp_bytes - sparse_cols_offset(C, n, nw)) / sizeof(uint16_t);
-    const uint32_t capacity = room > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)room;
+    const uint32_t capacity = sparse_capacity(Wp_bytes, C, n, nw);
     const dim3 rows((unsigned)((n + 3) / 4));
     hipLaunchKernelGGL(k_sparse_degree, rows, dim3(256), 0, s, W, n, nw, offsets);
     hipError_t e = hipGetLastError();
@@ -360,8 +427,7 @@ hipError_t launch_retrieve_sparse(const char *Wp, size_t Wp_bytes, int C, int L,
     a.summary = reinterpret_cast<const uint32_t *>(Wp + sparse_summary_offset(n));
     a.full = reinterpret_cast<const uint64_t *>(Wp + sparse_full_offset(C, n, nw));
     a.cols = reinterpret_cast<const uint16_t *>(Wp + sparse_cols_offset(C, n, nw));
-    const size_t room = (Wp_bytes - sparse_cols_offset(C, n, nw)) / sizeof(uint16_t);
-    a.capacity = room > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)room;
+    a.capacity = sparse_capacity(Wp_bytes, C, n, nw);
     a.sym_in = probes;
     a.bits_out = bits_out;
     a.sym_out = sym_out;
@@ -369,11 +435,28 @@ hipError_t launch_retrieve_sparse(const char *Wp, size_t Wp_bytes, int C, int L,
     a.K = K;
     a.C = C;
     a.L = L;
+    a.n = n;
     a.nw = nw;
     a.wpc = L / 32;
     a.max_iters = max_iters;
+    // LDS per wave: about 10 KiB at most (so that a compute unit keeps four 4-wave workgroups), less for
+    // small networks; the bit vectors of `group` clusters fit at once
+    int group = (2560 - kSparseList - nw) / nw;
+    if (group > C) group = C;
+    if (group < 1) group = 1;
+    a.group = group;
+    a.wave_words = sparse_wave_words(nw, group);
+    const size_t lds = (size_t)a.wave_words * kSparseWaves * sizeof(uint32_t);
     const int64_t blocks = (K + kSparseWaves - 1) / kSparseWaves;
-    hipLaunchKernelGGL(k_retrieve_sparse, dim3((unsigned)blocks), dim3(64 * kSparseWaves), 0, s, a);
+    const dim3 grid((unsigned)blocks), block(64 * kSparseWaves);
+    if (nw <= 64)
+        hipLaunchKernelGGL(k_retrieve_sparse<1>, grid, block, lds, s, a);
+    else if (nw <= 128)
+        hipLaunchKernelGGL(k_retrieve_sparse<2>, grid, block, lds, s, a);
+    else if (nw <= 256)
+        hipLaunchKernelGGL(k_retrieve_sparse<4>, grid, block, lds, s, a);
+    else
+        hipLaunchKernelGGL(k_retrieve_sparse<8>, grid, block, lds, s, a);
     return hipGetLastError();
 }
 
