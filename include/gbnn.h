@@ -63,7 +63,8 @@ size_t gbnn_w_row_words(int C, int L);
 /* Bytes of W: n * gbnn_w_row_words * 4.  0 if the shape is outside the limits. */
 size_t gbnn_w_bytes(int C, int L);
 /* Bytes of the device workspace that gbnn_prepare fills and gbnn_retrieve reads for this shape,
- * batch and rule (a multiple of 256, never 0 for a valid shape; about the size of W).  0 if an
+ * batch and rule (a multiple of 256, never 0 for a valid shape; about the size of W, of W with its
+ * clusters padded to the next power of two of at least 32 neurons where L is not one).  0 if an
  * argument is outside the limits. */
 size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule);
 
@@ -138,10 +139,12 @@ int gbnn_retrieve(const uint32_t *W, int C, int L, const uint8_t *V0, uint8_t *V
  * gbnn_retrieve for callers that cannot allocate device memory and so have no workspace to pass: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The table that
  * gbnn_prepare derives from W is built, on every call, in a device array that is part of the library
- * itself (about 8.1 MiB on every GPU the library runs on, held until the process ends), and the
+ * itself (about 8.6 MiB on every GPU the library runs on, held until the process ends), and the
  * retrieval then reads it there: gbnn_prepare followed by gbnn_retrieve, enqueued on `stream`, same
  * arguments, same results, and no allocation anywhere.
- *   Limit: n = C*L <= GBNN_STATIC_MAX_N, else GBNN_ERR_TOO_LARGE (nothing is enqueued).
+ *   Limit: n = C*L <= GBNN_STATIC_MAX_N, and, where L is not a power of two of at least 32, also
+ *   C*L' <= GBNN_STATIC_MAX_N for the next such number L' (the table is laid out for padded clusters);
+ *   else GBNN_ERR_TOO_LARGE (nothing is enqueued).
  *   All calls on one GPU share that one array: calls that overlap in time on one GPU (different
  *   streams or threads) race; order them on one stream.  The array keeps what the last call wrote;
  *   every word a call reads is rewritten by that call first.
@@ -201,15 +204,16 @@ int gbnn_retrieve_sparse(const void *Wp, size_t Wp_bytes, int C, int L, const in
 /* Static description of a status code (never NULL). */
 const char *gbnn_strerror(int code);
 
-/* Name of the kernel family gbnn_retrieve would run for this shape, rule and pointer alignment
+/* Name of the kernel family gbnn_retrieve would run for this shape and rule
  * ("half1" = two probes per wavefront, one packed word per lane, networks of up to 1024 neurons;
  * "wave1", "wave2", "wave4", "wave8" = one wavefront per probe with 1, 2, 4 or 8 packed words per lane;
- * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the family
- * reported for V0 = V_out = NULL.  Host only; for tests and reports.
- * The register-resident families need L to be a power of two in 32..2048 (every shape with such an
- * L is within their reach); the any-shape kernel is more than ten times slower.  A network whose L is not a power of two can be stored with L
- * rounded up (the extra neurons are never part of a message): retrieval then returns the same symbols,
- * and pass counts that can be larger by the pass that switches the extra neurons off. */
+ * "generic" = any shape), or NULL for invalid arguments.  gbnn_retrieve_symbols runs the same family.
+ * Host only; for tests and reports.
+ * The register-resident families hold a cluster in 2^k >= 32 neurons' worth of lanes; a cluster size L that
+ * is not such a number is padded to the next one inside the library (W, activity vectors and results keep
+ * their layout, results and pass counts are the same; the workspace grows accordingly).  They serve every
+ * shape whose padded network has clusters of at most 2048 and at most GBNN_MAX_N neurons in all, with V0
+ * and V_out at any alignment; the any-shape kernel, more than ten times slower, serves the rest. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
 
 /*

@@ -11,7 +11,8 @@ using namespace gbnn;
 // flags).  In host code this name only stands for the symbol; the array's address on a device comes
 // from hipGetSymbolAddress (static_scratch below).
 constexpr size_t kStaticScratchBytes =
-    ((size_t)(GBNN_STATIC_MAX_N + GBNN_MAX_C + 2) * (GBNN_STATIC_MAX_N / 32) * 4 + 255) / 256 * 256 + 256;
+    ((size_t)(GBNN_STATIC_MAX_N + GBNN_MAX_C + 2) * (GBNN_STATIC_MAX_N / 32) * 4 + 255) / 256 * 256 + 256 +
+    (size_t)GBNN_MAX_C * (GBNN_STATIC_MAX_N / 32) * 4;  // (+ the canonical summaries of a padded network)
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
@@ -53,7 +54,8 @@ int pick_path(int C, int L, int rule, const void *V0, const void *Vout)
 {
     const int family = g_retrieve_family.load(std::memory_order_relaxed);
     if (family == GBNN_FAMILY_GENERIC) return 0;
-    if (!aligned(V0, 16) || !aligned(Vout, 16)) return 0;  // (the message boundary passes nullptr: no constraint)
+    (void)V0;
+    (void)Vout;  // (any alignment: the kernels load and store the activity in pieces of 16, 4 or 1 bytes)
     if (family != GBNN_FAMILY_WAVE && half_wave_serves(C, L)) return kHalfPath;
     (void)rule;
     return wave_words_per_lane(C, L);
@@ -63,14 +65,21 @@ int pick_path(int C, int L, int rule, const void *V0, const void *Vout)
 int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K, int rule, int gamma, int max_iters,
                     int32_t *iters_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, (C * L + 31) / 32))
-        return GBNN_ERR_WORKSPACE;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L)) return GBNN_ERR_WORKSPACE;
     if (K == 0) return GBNN_OK;
+    const Geometry g = geometry(C, L);
+    const char *ws = static_cast<const char *>(workspace);
     a.W = W;
     a.nw = (C * L + 31) / 32;
-    a.Wb = static_cast<const uint32_t *>(workspace);
-    a.has = reinterpret_cast<const uint32_t *>(static_cast<const char *>(workspace) + workspace_has_offset(C, L, a.nw));
-    a.full = reinterpret_cast<const uint64_t *>(static_cast<const char *>(workspace) + workspace_full_offset(C, L, a.nw));
+    a.Lp = g.Lp;
+    a.np = g.np;
+    a.nwp = g.nwp;
+    a.Wb = reinterpret_cast<const uint32_t *>(ws);
+    a.has = reinterpret_cast<const uint32_t *>(ws + workspace_has_offset(C, L));
+    a.hasc = g.padded ? reinterpret_cast<const uint32_t *>(ws + workspace_canonical_offset(C, L)) : a.has;
+    a.full = reinterpret_cast<const uint64_t *>(ws + workspace_full_offset(C, L));
+    a.align = (L % 16 == 0 && aligned(a.V0, 16) && aligned(a.Vout, 16)) ? 16
+              : (L % 4 == 0 && aligned(a.V0, 4) && aligned(a.Vout, 4)) ? 4 : 1;
     a.iters = iters_out;
     a.K = K;
     a.C = C;
@@ -106,7 +115,7 @@ size_t gbnn_w_bytes(int C, int L)
 size_t gbnn_workspace_bytes(int C, int L, int64_t K, int rule)
 {
     if (!shape_ok(C, L) || K < 0 || K > GBNN_MAX_K || !rule_ok(rule)) return 0;
-    return workspace_total_bytes(C, L, (int)gbnn_w_row_words(C, L));
+    return workspace_total_bytes(C, L);
 }
 
 int gbnn_store(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M, int32_t *status, void *stream)
@@ -125,13 +134,8 @@ int gbnn_prepare(const uint32_t *W, int C, int L, void *workspace, size_t worksp
     if (!shape_ok(C, L)) return GBNN_ERR_SHAPE;
     if (!W) return GBNN_ERR_NULL;
     const int nw = (int)gbnn_w_row_words(C, L);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, nw))
-        return GBNN_ERR_WORKSPACE;
-    char *ws = static_cast<char *>(workspace);
-    const hipError_t e =
-        launch_prepare(W, C, L, nw, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
-                       reinterpret_cast<uint32_t *>(ws), reinterpret_cast<uint64_t *>(ws + workspace_full_offset(C, L, nw)),
-                       static_cast<hipStream_t>(stream));
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L)) return GBNN_ERR_WORKSPACE;
+    const hipError_t e = launch_prepare(W, C, L, nw, static_cast<char *>(workspace), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
@@ -141,13 +145,9 @@ int gbnn_store_update(uint32_t *W, int C, int L, const int32_t *msgs, int64_t M,
     if (!shape_ok(C, L) || M < 0) return GBNN_ERR_SHAPE;
     if (!W || (M > 0 && !msgs)) return GBNN_ERR_NULL;
     const int nw = (int)gbnn_w_row_words(C, L);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L, nw))
-        return GBNN_ERR_WORKSPACE;
-    char *ws = static_cast<char *>(workspace);
-    const hipError_t e = launch_store_update(
-        W, C, L, nw, msgs, M, status, reinterpret_cast<uint32_t *>(ws + workspace_has_offset(C, L, nw)),
-        reinterpret_cast<uint32_t *>(ws), reinterpret_cast<uint64_t *>(ws + workspace_full_offset(C, L, nw)),
-        static_cast<hipStream_t>(stream));
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < workspace_total_bytes(C, L)) return GBNN_ERR_WORKSPACE;
+    const hipError_t e = launch_store_update(W, C, L, nw, msgs, M, status, static_cast<char *>(workspace),
+                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
@@ -175,7 +175,8 @@ int gbnn_retrieve_static(const uint32_t *W, int C, int L, const uint8_t *V0, uin
     if (max_iters < 1) return GBNN_ERR_ITERS;
     if (!W || (K > 0 && (!V0 || !V_out))) return GBNN_ERR_NULL;
     const int nw = (int)gbnn_w_row_words(C, L);
-    if (C * L > GBNN_STATIC_MAX_N || workspace_total_bytes(C, L, nw) > kStaticScratchBytes) return GBNN_ERR_TOO_LARGE;
+    (void)nw;
+    if (C * L > GBNN_STATIC_MAX_N || workspace_total_bytes(C, L) > kStaticScratchBytes) return GBNN_ERR_TOO_LARGE;
     if (K == 0) return GBNN_OK;
     void *ws = static_scratch();
     if (!ws) return GBNN_ERR_DEVICE;
@@ -261,7 +262,7 @@ const char *gbnn_strerror(int code)
     case GBNN_ERR_ITERS: return "max_iters must be at least 1";
     case GBNN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than gbnn_workspace_bytes";
     case GBNN_ERR_DEVICE: return "the HIP runtime refused a kernel launch";
-    case GBNN_ERR_TOO_LARGE: return "gbnn_retrieve_static serves networks of up to 8192 neurons";
+    case GBNN_ERR_TOO_LARGE: return "gbnn_retrieve_static serves networks of up to 8192 neurons (clusters padded to a power of two)";
     default: return "unknown status code";
     }
 }

@@ -39,6 +39,97 @@ __device__ __forceinline__ uint4 spread16(uint32_t h)
     return make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4((h >> 12) & 15u));
 }
 
+// Padded clusters: a register kernel holds a cluster of L neurons in Lp / 32 words, Lp = 2^k >= L.  The bits
+// of word number `wi` of a cluster (its neurons 32 wi .. 32 wi + 31) that are neurons at all:
+__device__ __forceinline__ uint32_t pad_mask(uint32_t L, uint32_t wi)
+{
+    const int left = (int)L - 32 * (int)wi;
+    return left >= 32 ? 0xFFFFFFFFu : left <= 0 ? 0u : (1u << left) - 1u;
+}
+// 16 bytes at any alignment (the hardware takes unaligned multi-word accesses to global memory).
+typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(1)));
+__device__ __forceinline__ uint4 load16_unaligned(const uint8_t *p)
+{
+    const u32x4_unaligned x = *reinterpret_cast<const u32x4_unaligned *>(p);
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ void store16_unaligned(uint8_t *p, uint4 s)
+{
+    u32x4_unaligned x = {s.x, s.y, s.z, s.w};
+    *reinterpret_cast<u32x4_unaligned *>(p) = x;
+}
+// The first `count` (< 16) of 16 bytes, the rest zero: byte loads, none past the last one asked for.
+__device__ __forceinline__ uint4 load_bytes(const uint8_t *p, uint32_t count)
+{
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int b = 0; b < 15; ++b)
+        if ((uint32_t)b < count) d[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
+    return make_uint4(d[0], d[1], d[2], d[3]);
+}
+// The 32 activity bytes cl[32 wi .. 32 wi + 31] of a cluster (cl = its first byte, any alignment) as 32
+// bits; bytes past the end of the cluster (L) give 0.  A 16-byte piece that straddles the end of the cluster
+// is read whole -- what follows in memory is the next cluster or the next probe -- unless `last`: the
+// cluster is the last one of the last probe, and nothing past its end is touched.
+__device__ __forceinline__ uint32_t load_cluster_word(const uint8_t *cl, uint32_t L, uint32_t wi, bool last)
+{
+    const uint32_t l0 = 32u * wi;
+    uint4 p[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t at = l0 + 16u * h;
+        p[h] = make_uint4(0u, 0u, 0u, 0u);
+        if (at + 16u <= L || (at < L && !last))
+            p[h] = load16_unaligned(cl + at);
+        else if (at < L)
+            p[h] = load_bytes(cl + at, L - at);
+    }
+    return (pack16(p[0]) | (pack16(p[1]) << 16)) & pad_mask(L, wi);
+}
+// ... and back: the 32 bits of v as bytes cl[32 wi ..], those within the cluster only.  Whole 16-byte pieces
+// at any alignment; a piece cut short by the end of the cluster in 4-byte pieces if `by4` (cl and L are
+// multiples of 4), else byte by byte.
+__device__ __forceinline__ void store_cluster_word(uint8_t *cl, uint32_t L, uint32_t wi, bool by4, uint32_t v)
+{
+    const uint32_t l0 = 32u * wi;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t at = l0 + 16u * h;
+        const uint4 s = spread16((v >> (16 * h)) & 0xFFFFu);
+        if (at + 16u <= L) {
+            store16_unaligned(cl + at, s);
+        } else if (at < L) {
+            const uint32_t d[4] = {s.x, s.y, s.z, s.w};
+            if (by4) {
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+                    if (at + 4u * q < L) *reinterpret_cast<uint32_t *>(cl + at + 4 * q) = d[q];
+            } else {
+#pragma unroll
+                for (int b = 0; b < 15; ++b)
+                    if (at + (uint32_t)b < L) cl[at + b] = (uint8_t)(d[b >> 2] >> (8 * (b & 3)));
+            }
+        }
+    }
+}
+// The packed result of a padded kernel at the message boundary when clusters share words of it (L not a
+// multiple of 32): word `wi` of cluster c, value v (bits past the end of the cluster are zero), ORed into the
+// canonical bit positions c*L + 32 wi .. of a bit vector in LDS that the wave has zeroed.
+__device__ __forceinline__ void or_cluster_word(uint32_t *out, uint32_t c, uint32_t L, uint32_t wi, uint32_t v)
+{
+    if (32u * wi >= L || v == 0u) return;
+    const uint32_t pos = c * L + 32u * wi, sh = pos & 31u;
+    atomicOr(out + (pos >> 5), v << sh);
+    if (sh && (v >> (32u - sh))) atomicOr(out + (pos >> 5) + 1, v >> (32u - sh));
+}
+// LDS traffic between the lanes of one wave: make earlier writes visible to later reads.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // A wave-uniform lane mask read as a per-lane flag (no vector arithmetic: the mask is the condition).
 __device__ __forceinline__ bool lane_of(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 

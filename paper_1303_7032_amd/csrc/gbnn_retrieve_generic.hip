@@ -53,7 +53,7 @@ struct G {
             const int cnt = cluster_count(c);
             for (int w = lane; w < a.nw; w += 64) R[w] = own_mask(c, a.L, w);
             if (cnt == a.L) {
-                const uint32_t *row = a.has + (int64_t)c * a.nw;
+                const uint32_t *row = a.hasc + (int64_t)c * a.nw;
                 for (int w = lane; w < a.nw; w += 64) R[w] |= row[w];
             } else if (cnt > 0) {
                 for (int ww = first_word(c); ww <= last_word(c); ++ww) {

@@ -451,8 +451,11 @@ __device__ __forceinline__ void candidate_passes_h(const HCtx &x, uint32_t probe
 template <int RULE, int LGL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k_retrieve_half(RetrieveArgs a)
 {
-    // high counter digits of sum-of-sum, one column per lane and wave (unused by the other rules)
-    __shared__ uint32_t sos_hi[RULE == GBNN_SUM_OF_SUM ? 4 * (kPlanes - kRegPlanes) * 64 : 1];
+    // LDS, a quarter per wave: the high counter digits of sum-of-sum, one column per lane; for every rule, at
+    // the end, the packed results of a network with padded clusters on their way to the canonical layout
+    constexpr int kLdsWords = RULE == GBNN_SUM_OF_SUM ? 4 * (kPlanes - kRegPlanes) * 64 : 4 * 64;
+    __shared__ uint32_t lds_words[kLdsWords];
+    uint32_t *sos_hi = lds_words;
     const int wpb = (int)(blockDim.x >> 6);  // waves per workgroup
     const int64_t pair = (int64_t)blockIdx.x * wpb + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t k0 = pair * 2;  // probes k0 (lower half) and k0 + 1 (upper half)
@@ -464,14 +467,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     x.gl = lane & 31u;
     x.upperm = upper ? 0xFFFFFFFFu : 0u;
     x.basev = upper ? 128u : 0u;
-    x.rowbytes = (uint32_t)a.nw * 4u;
-    x.nrows = (uint32_t)a.n;
-    x.zero_row = (uint32_t)(a.n + a.C);
+    x.rowbytes = (uint32_t)a.nwp * 4u;
+    x.nrows = (uint32_t)a.np;
+    x.zero_row = (uint32_t)(a.np + a.C);
     x.ones_row = x.zero_row + 1u;
     x.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
-                                               (int)((uint32_t)(a.n + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
+                                               (int)((uint32_t)(a.np + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
     const bool pvalid = k0 + (upper ? 1 : 0) < a.K;  // K odd: the last wave carries one probe
-    x.valid = pvalid && x.gl < (uint32_t)a.nw;
+    x.valid = pvalid && x.gl < (uint32_t)a.nwp;
     x.islead = x.valid && (x.gl & ((1u << LGL) - 1u)) == 0u;
     x.woffb = x.valid ? x.gl * 4u : 0u;
     x.myc = x.gl >> LGL;
@@ -482,14 +485,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     const int64_t kmine = k0 + second;
     const uint32_t boff = (upper ? (uint32_t)a.n : 0u) + x.woffb * 8u;  // this lane's bytes, from the first probe of the pair
     constexpr uint32_t kInCluster = (1u << LGL) - 1u;
+    const bool padded = a.Lp != a.L;  // clusters of L neurons held in the words of Lp = 2^k > L
+    const bool plain_io = !padded && a.align == 16;  // activity as two 16-byte pieces per word, no piece past a cluster's end
+    // the bits of this lane's word that are neurons (all of them unless the clusters are padded)
+    const uint32_t pmask = !x.valid ? 0u : padded ? pad_mask((uint32_t)a.L, x.gl & kInCluster) : 0xFFFFFFFFu;
     uint32_t v;
     if (a.sym_in) {
         const int32_t *sym = a.sym_in + probe_offset(k0, a.C) + second * a.C;
         v = x.valid ? symbol_word(sym[x.myc], (uint32_t)a.L, x.gl & kInCluster) : 0u;
-    } else {
+    } else if (plain_io) {
         const uint4 *p = reinterpret_cast<const uint4 *>(a.V0 + probe_offset(k0, a.n) + (x.valid ? boff : 0u));
         const uint4 lo = p[0], hi = p[1];
         v = x.valid ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
+    } else {
+        const uint8_t *src = a.V0 + probe_offset(kmine, a.n) + x.myc * (uint32_t)a.L;
+        v = x.valid ? load_cluster_word(src, (uint32_t)a.L, x.gl & kInCluster, kmine == a.K - 1 && x.myc == (uint32_t)a.C - 1u) : 0u;
     }
 
     int it0 = 0, it1 = 0;
@@ -506,7 +516,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
             uint32_t pw = v;
             const uint64_t full = *a.full;  // clusters whose summary row is all ones: it changes nothing, not fetched
             uint64_t summask = ballot(erased && x.islead && !((full >> (x.myc & 63u)) & 1ull));
-            if (erased) v = 0xFFFFFFFFu;
+            if (erased) v = pmask;
             acc = v;
             fetch_and_apply_h<LGL>(x, pw, summask, acc);
             d = acc ^ v;
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
                 // their rows over the erased clusters.
                 uint32_t pw = v;
                 uint64_t summask = 0;
-                acc = erased ? 0xFFFFFFFFu : v;
+                acc = erased ? pmask : v;
                 fetch_and_apply_h<LGL>(x, pw, summask, acc);
                 acc = erased ? acc : v;
                 d = erased ? 1u : 0u;  // known clusters have just been applied: clean
@@ -612,7 +622,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
             }
             // Eq. (4)-(5): per cluster keep the neurons whose score is the cluster maximum, found
             // digit by digit from the top.
-            uint32_t cand = x.valid ? 0xFFFFFFFFu : 0u;
+            uint32_t cand = pmask;
             for (int q = P - 1; q >= kRegPlanes; --q) {
                 const uint32_t tt = cand & pl.get_hi(q, 0);
                 if (group_or<LGL>(tt) != 0u) cand = tt;
@@ -642,15 +652,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     // ---- result store
     if (a.iters && x.gl == 0u && pvalid) a.iters[kmine] = upper ? it1 : it0;
     if (a.sym_in) {
-        if (a.bits_out && x.valid) a.bits_out[probe_offset(k0, a.nw) + second * a.nw + x.gl] = v;
+        if (a.bits_out) {
+            uint32_t *out = a.bits_out + probe_offset(k0, a.nw) + second * a.nw;  // (this lane's probe)
+            if (!padded) {
+                if (x.valid) out[x.gl] = v;
+            } else if ((a.L & 31) == 0) {
+                // whole words: the words of a cluster that exist go to their canonical places
+                const uint32_t wi = x.gl & kInCluster;
+                if (x.valid && 32u * wi < (uint32_t)a.L) out[x.myc * ((uint32_t)a.L >> 5) + wi] = v;
+            } else {
+                // clusters share words: the canonical bit vector of each probe is put together in LDS
+                uint32_t *canon = lds_words + (threadIdx.x >> 6) * (kLdsWords / 4) + (upper ? 32u : 0u);
+                if (x.gl < (uint32_t)a.nw) canon[x.gl] = 0u;
+                wave_lds_sync();
+                if (x.valid) or_cluster_word(canon, x.myc, (uint32_t)a.L, x.gl & kInCluster, v);
+                wave_lds_sync();
+                if (pvalid && x.gl < (uint32_t)a.nw) out[x.gl] = canon[x.gl];
+            }
+        }
         if (a.sym_out) {
             const int32_t sy = cluster_symbol<LGL>(v, x.gl & kInCluster);
             if (x.islead) a.sym_out[probe_offset(k0, a.C) + second * a.C + x.myc] = sy;
         }
     } else if (x.valid) {
-        uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + probe_offset(k0, a.n) + boff);
-        dst[0] = spread16(v & 0xFFFFu);
-        dst[1] = spread16(v >> 16);
+        if (plain_io) {
+            uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + probe_offset(k0, a.n) + boff);
+            dst[0] = spread16(v & 0xFFFFu);
+            dst[1] = spread16(v >> 16);
+        } else {
+            store_cluster_word(a.Vout + probe_offset(kmine, a.n) + x.myc * (uint32_t)a.L, (uint32_t)a.L, x.gl & kInCluster,
+                               a.align >= 4, v);
+        }
     }
 }
 
@@ -680,15 +712,16 @@ hipError_t launch_one_h(const RetrieveArgs &a, hipStream_t s)
 // Shapes served: L a power of two >= 32 and at most 32 packed words per probe.
 bool half_wave_serves(int C, int L)
 {
-    if (L < 32 || (L & (L - 1)) != 0) return false;
-    return C * (L / 32) <= 32;
+    const Geometry g = geometry(C, L);  // (clusters padded to a power of two of at least 32 neurons)
+    if (g.Lp < 32 || (g.Lp & (g.Lp - 1)) != 0 || g.Lp < L) return false;
+    return g.nwp <= 32;
 }
 
 hipError_t launch_retrieve_half(const RetrieveArgs &a, hipStream_t s)
 {
     if (a.K == 0) return hipSuccess;
     if (!half_wave_serves(a.C, a.L)) return hipErrorInvalidValue;
-    switch (a.L / 32) {  // lanes per cluster; C >= 2 keeps it at 16 or below
+    switch (a.Lp / 32) {  // lanes per cluster; C >= 2 keeps it at 16 or below
     case 1: return launch_one_h<0>(a, s);
     case 2: return launch_one_h<1>(a, s);
     case 4: return launch_one_h<2>(a, s);

@@ -672,24 +672,34 @@ k_retrieve_wave(RetrieveArgs a)
 {
     constexpr int LW = 1 << LG;
     constexpr int CPS = 64 / LW;  // clusters per slot
-    // high counter digits of sum-of-sum, one column per lane and wave (unused by the other rules)
-    __shared__ uint32_t sos_hi[RULE == GBNN_SUM_OF_SUM ? 4 * (kPlanes - kRegPlanes) * NW * 64 : 1];
+    // LDS, a quarter per wave: the high counter digits of sum-of-sum, one column per lane; for every rule, at
+    // the end, the packed result of a network with padded clusters on its way to the canonical layout
+    constexpr int kLdsWords = RULE == GBNN_SUM_OF_SUM ? 4 * (kPlanes - kRegPlanes) * NW * 64 : 4 * NW * 64;
+    __shared__ uint32_t lds_words[kLdsWords];
+    uint32_t *sos_hi = lds_words;
     Ctx<NW> x;
-    x.rowbytes = (uint32_t)a.nw * 4u;
-    x.nrows = (uint32_t)a.n;
+    x.rowbytes = (uint32_t)a.nwp * 4u;
+    x.nrows = (uint32_t)a.np;
     x.nclusters = (uint32_t)a.C;
     x.wbrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Wb), 0,
-                                                 (int)((uint32_t)(a.n + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
+                                                 (int)((uint32_t)(a.np + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
+    const bool padded = a.Lp != a.L;  // clusters of L neurons held in the words of Lp = 2^k > L
+    const bool plain_io = !padded && a.align == 16;  // activity as two 16-byte pieces per word, no piece past a cluster's end
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
-        x.valid[t] = (t * 64 + x.lane) < a.nw;
+        x.valid[t] = (t * 64 + x.lane) < a.nwp;
         x.islead[t] = x.valid[t] && (x.lane & (LW - 1)) == 0;
         x.woffb[t] = x.valid[t] ? (uint32_t)(t * 64 + x.lane) * 4u : 0u;
         x.myc[t] = x.valid[t] ? (uint32_t)(t * CPS + (x.lane >> LG)) : 0xFFFFu;
         x.bit0[t] = (uint32_t)(t * 64 + x.lane) << 5;
         x.validmask[t] = ballot(x.valid[t]);
     }
+    // the bits of this lane's words that are neurons (all of them unless the clusters are padded)
+    uint32_t pmask[NW];
+#pragma unroll
+    for (int t = 0; t < NW; ++t)
+        pmask[t] = !x.valid[t] ? 0u : padded ? pad_mask((uint32_t)a.L, (uint32_t)x.lane & (LW - 1)) : 0xFFFFFFFFu;
     // One probe per wave: the hardware's workgroup dispatcher balances the uneven probe times (a grid of
     // resident waves striding over the probes measured 1.1-2x slower).
     const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -702,7 +712,7 @@ k_retrieve_wave(RetrieveArgs a)
 #pragma unroll
             for (int t = 0; t < NW; ++t)
                 v[t] = x.valid[t] ? symbol_word(sym[x.myc[t]], (uint32_t)a.L, (uint32_t)x.lane & (LW - 1)) : 0u;
-        } else {
+        } else if (plain_io) {
             const uint8_t *src = a.V0 + probe_offset(k, a.n);
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
@@ -711,6 +721,13 @@ k_retrieve_wave(RetrieveArgs a)
                 const uint4 hi = p[1];
                 v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
             }
+        } else {
+            const uint8_t *src = a.V0 + probe_offset(k, a.n);
+#pragma unroll
+            for (int t = 0; t < NW; ++t)
+                v[t] = x.valid[t] ? load_cluster_word(src + x.myc[t] * (uint32_t)a.L, (uint32_t)a.L, (uint32_t)x.lane & (LW - 1),
+                                                      k == a.K - 1 && x.myc[t] == x.nclusters - 1u)
+                                  : 0u;
         }
 
         int it = 0;
@@ -745,7 +762,7 @@ k_retrieve_wave(RetrieveArgs a)
                     // (a summary row that is all ones changes nothing: not fetched)
                     summask[t] = ballot(erased[t] && x.islead[t] && !((full >> (x.myc[t] & 63u)) & 1ull));
                     anysum |= summask[t];
-                    if (erased[t]) v[t] = 0xFFFFFFFFu;
+                    if (erased[t]) v[t] = pmask[t];
                     acc[t] = v[t];
                 }
                 if (contract && !anysum)
@@ -761,7 +778,7 @@ k_retrieve_wave(RetrieveArgs a)
                     // clusters.
 #pragma unroll
                     for (int t = 0; t < NW; ++t)
-                        acc[t] = erased[t] ? 0xFFFFFFFFu : 0u;  // (known clusters are restored below: their lanes fetch nothing)
+                        acc[t] = erased[t] ? pmask[t] : 0u;  // (known clusters are restored below: their lanes fetch nothing)
                     and_single_rows<NW>(x, v, acc);
 #pragma unroll
                     for (int t = 0; t < NW; ++t) {
@@ -865,7 +882,7 @@ k_retrieve_wave(RetrieveArgs a)
                 // found digit by digit from the top.
                 uint32_t cand[NW];
 #pragma unroll
-                for (int u = 0; u < NW; ++u) cand[u] = x.valid[u] ? 0xFFFFFFFFu : 0u;
+                for (int u = 0; u < NW; ++u) cand[u] = pmask[u];
                 for (int q = P - 1; q >= kRegPlanes; --q)
 #pragma unroll
                     for (int u = 0; u < NW; ++u) {
@@ -895,9 +912,28 @@ k_retrieve_wave(RetrieveArgs a)
         if (a.iters && x.lane == 0) a.iters[k] = it;
         if (a.sym_in) {
             if (a.bits_out) {
+                uint32_t *out = a.bits_out + probe_offset(k, a.nw);
+                if (!padded) {
 #pragma unroll
-                for (int t = 0; t < NW; ++t)
-                    if (x.valid[t]) a.bits_out[probe_offset(k, a.nw) + t * 64 + x.lane] = v[t];
+                    for (int t = 0; t < NW; ++t)
+                        if (x.valid[t]) out[t * 64 + x.lane] = v[t];
+                } else if ((a.L & 31) == 0) {
+                    // whole words: the words of a cluster that exist go to their canonical places
+                    const uint32_t wi = (uint32_t)x.lane & (LW - 1);
+#pragma unroll
+                    for (int t = 0; t < NW; ++t)
+                        if (x.valid[t] && 32u * wi < (uint32_t)a.L) out[x.myc[t] * ((uint32_t)a.L >> 5) + wi] = v[t];
+                } else {
+                    // clusters share words: the canonical bit vector is put together in LDS
+                    uint32_t *canon = lds_words + (threadIdx.x >> 6) * (kLdsWords / 4);
+                    for (int w = x.lane; w < a.nw; w += 64) canon[w] = 0u;
+                    wave_lds_sync();
+#pragma unroll
+                    for (int t = 0; t < NW; ++t)
+                        if (x.valid[t]) or_cluster_word(canon, x.myc[t], (uint32_t)a.L, (uint32_t)x.lane & (LW - 1), v[t]);
+                    wave_lds_sync();
+                    for (int w = x.lane; w < a.nw; w += 64) out[w] = canon[w];
+                }
             }
             if (a.sym_out) {
 #pragma unroll
@@ -906,7 +942,7 @@ k_retrieve_wave(RetrieveArgs a)
                     if (x.islead[t]) a.sym_out[probe_offset(k, a.C) + x.myc[t]] = sy;
                 }
             }
-        } else {
+        } else if (plain_io) {
             uint8_t *dstb = a.Vout + probe_offset(k, a.n);
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
@@ -916,6 +952,13 @@ k_retrieve_wave(RetrieveArgs a)
                     dst[1] = spread16(v[t] >> 16);
                 }
             }
+        } else {
+            uint8_t *dstb = a.Vout + probe_offset(k, a.n);
+#pragma unroll
+            for (int t = 0; t < NW; ++t)
+                if (x.valid[t])
+                    store_cluster_word(dstb + x.myc[t] * (uint32_t)a.L, (uint32_t)a.L, (uint32_t)x.lane & (LW - 1),
+                                       a.align >= 4, v[t]);
         }
     }
 }
@@ -987,8 +1030,9 @@ hipError_t launch_nw(const RetrieveArgs &a, int log2lw, hipStream_t s)
 
 int wave_words_per_lane(int C, int L)
 {
-    if (L < 32 || L > 2048 || (L & (L - 1)) != 0) return 0;
-    const int nw = C * (L / 32);
+    const Geometry g = geometry(C, L);
+    if (g.Lp < 32 || g.Lp > 2048 || (g.Lp & (g.Lp - 1)) != 0 || g.Lp < L) return 0;  // (not served: geometry() left L as it is)
+    const int nw = g.nwp;
     if (nw <= 64) return 1;
     if (nw <= 128) return 2;
     if (nw <= 256) return 4;
@@ -999,7 +1043,7 @@ int wave_words_per_lane(int C, int L)
 hipError_t launch_retrieve_wave(const RetrieveArgs &a, int words_per_lane, hipStream_t s)
 {
     if (a.K == 0) return hipSuccess;
-    const int lw = a.L / 32;
+    const int lw = a.Lp / 32;
     int log2lw = 0;
     while ((1 << log2lw) < lw) ++log2lw;
     switch (words_per_lane) {

@@ -24,14 +24,6 @@ namespace {
 
 constexpr int kSparseWaves = 4;                        // probes per workgroup
 
-// LDS traffic between the lanes of one wave: make earlier writes visible to later reads.
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 {
 #pragma unroll

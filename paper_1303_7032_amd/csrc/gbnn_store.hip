@@ -43,8 +43,10 @@ __global__ __launch_bounds__(256) void k_store(uint32_t *W, int C, int L, int nw
 // thread of (message m, cluster c) sets, for the message's neuron a of cluster c and its neuron b of every
 // other cluster, bit b of row a in W and in the table's copy of W, and bit b of the summary row of cluster
 // c (b now has a neighbour in c).  The own-cluster blocks and own bits of the table stay as they are.
-__global__ __launch_bounds__(256) void k_store_update(uint32_t *W, uint32_t *Wb, uint32_t *has, int C, int L, int nw,
-                                                      const int32_t *__restrict__ msgs, int64_t M,
+// The table is in the layout of the padded network (clusters of Lp neurons, rows of nwp words); hasc, if
+// not null, is the copy of the summaries in the canonical layout.
+__global__ __launch_bounds__(256) void k_store_update(uint32_t *W, uint32_t *Wb, uint32_t *has, uint32_t *hasc, int C, int L,
+                                                      int nw, int Lp, int nwp, const int32_t *__restrict__ msgs, int64_t M,
                                                       int32_t *__restrict__ status)
 {
     const int64_t total = M * C;
@@ -60,14 +62,16 @@ __global__ __launch_bounds__(256) void k_store_update(uint32_t *W, uint32_t *Wb,
             continue;
         }
         const int64_t row = ((int64_t)c * L + sym[c]) * nw;
+        const int64_t rowp = ((int64_t)c * Lp + sym[c]) * nwp;
         for (int c2 = 0; c2 < C; ++c2) {
             if (c2 == c) continue;
-            const int col = c2 * L + sym[c2];
-            const uint32_t bit = 1u << (col & 31);
-            const int w = col >> 5;
+            const int col = c2 * L + sym[c2], colp = c2 * Lp + sym[c2];
+            const uint32_t bit = 1u << (col & 31), bitp = 1u << (colp & 31);
+            const int w = col >> 5, wp = colp >> 5;
             if (!(W[row + w] & bit)) atomicOr(W + row + w, bit);
-            if (!(Wb[row + w] & bit)) atomicOr(Wb + row + w, bit);
-            if (!(has[(int64_t)c * nw + w] & bit)) atomicOr(has + (int64_t)c * nw + w, bit);
+            if (!(Wb[rowp + wp] & bitp)) atomicOr(Wb + rowp + wp, bitp);
+            if (!(has[(int64_t)c * nwp + wp] & bitp)) atomicOr(has + (int64_t)c * nwp + wp, bitp);
+            if (hasc && !(hasc[(int64_t)c * nw + w] & bit)) atomicOr(hasc + (int64_t)c * nw + w, bit);
         }
     }
 }
@@ -215,8 +219,10 @@ __global__ __launch_bounds__(64 * kSumRows) void k_cluster_summary(const uint32_
 // full = bit c set iff the summary row of cluster c has every neuron's bit: then every neuron has a
 // neighbour in c (or is in c), and a fully active cluster c switches nobody off.  With the densities the
 // method works at this is the rule, and retrieval skips those rows.  One workgroup of 16 waves; a wave
-// checks the rows of clusters wave, wave + 16, ..., its lanes striding over the words.
-__global__ __launch_bounds__(1024) void k_summary_full(const uint32_t *__restrict__ has, int C, int n, int nw,
+// checks the rows of clusters wave, wave + 16, ..., its lanes striding over the words.  The rows may be in
+// the layout of a padded network (clusters of Lp >= L neurons, Lp a multiple of 32): only the first L
+// neurons of a cluster exist.  The other 31 words of the 256-byte block of flags are set to zero.
+__global__ __launch_bounds__(1024) void k_summary_full(const uint32_t *__restrict__ has, int C, int L, int Lp, int n, int nw,
                                                        uint64_t *__restrict__ full)
 {
     __shared__ uint32_t row_full[GBNN_MAX_C];
@@ -225,8 +231,9 @@ __global__ __launch_bounds__(1024) void k_summary_full(const uint32_t *__restric
         const uint32_t *row = has + (int64_t)c * nw;
         bool all = true;
         for (int w = lane; w < nw; w += 64) {
-            const int bits = n - 32 * w;  // neurons in this word
-            const uint32_t need = bits >= 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+            int bits = n - 32 * w;  // neurons in this word
+            if (Lp != L) bits = L - 32 * (w % (Lp / 32));
+            const uint32_t need = bits >= 32 ? 0xFFFFFFFFu : bits <= 0 ? 0u : ((1u << bits) - 1u);
             all = all && (row[w] & need) == need;
         }
         const bool every = ballot(!all) == 0;
@@ -236,6 +243,7 @@ __global__ __launch_bounds__(1024) void k_summary_full(const uint32_t *__restric
     if (threadIdx.x < 64) {
         const uint64_t m = ballot(lane < C && row_full[lane < C ? lane : 0] != 0u);
         if (lane == 0) *full = m;
+        if (lane >= 1 && lane < 32) full[lane] = 0ull;
     }
 }
 
@@ -253,6 +261,44 @@ __global__ __launch_bounds__(256) void k_fill_blocks(const uint32_t *__restrict_
         const int j = (int)(t / nw);
         const int w = (int)(t - (int64_t)j * nw);
         Wb[t] = W[t] | own_mask(j / L, L, w);
+    }
+}
+
+// The table of a padded network from the canonical W: row c*Lp + l (l < L) gets, for every padded cluster
+// c2, the L bits of row c*L + l of W that belong to c2 (all ones for c2 = c), 32 at a time from two
+// neighbouring words of W; rows and bits of neurons that do not exist are zero.  Also fills the all-zero
+// row of the table and the all-one row that follows it.
+__global__ __launch_bounds__(256) void k_fill_padded(const uint32_t *__restrict__ W, int L, int nw, int Lp, int nwp,
+                                                     int64_t words, uint32_t *__restrict__ Wb,
+                                                     uint32_t *__restrict__ zero_row)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int wpc = Lp / 32;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nwp; t += stride) {
+        zero_row[t] = 0u;
+        zero_row[nwp + t] = 0xFFFFFFFFu;
+    }
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < words; t += stride) {
+        const int jp = (int)(t / nwp);
+        const int wp = (int)(t - (int64_t)jp * nwp);
+        const int c = jp / Lp, l = jp - c * Lp;
+        const int c2 = wp / wpc, l2 = (wp - c2 * wpc) * 32;  // this word: neurons l2 .. l2 + 31 of cluster c2
+        uint32_t out = 0u;
+        if (l < L && l2 < L) {
+            const int count = L - l2 < 32 ? L - l2 : 32;
+            const uint32_t keep = count == 32 ? 0xFFFFFFFFu : ((1u << count) - 1u);
+            if (c2 == c) {
+                out = keep;
+            } else {
+                const int bit = c2 * L + l2;  // first of `count` consecutive bits of the canonical row
+                const uint32_t *row = W + (int64_t)(c * L + l) * nw;
+                const int w0 = bit >> 5, sh = bit & 31;
+                uint32_t lo = row[w0] >> sh;
+                if (sh && w0 + 1 < nw) lo |= row[w0 + 1] << (32 - sh);
+                out = lo & keep;
+            }
+        }
+        Wb[t] = out;
     }
 }
 
@@ -291,16 +337,22 @@ hipError_t launch_store(uint32_t *W, int C, int L, int nw, const int32_t *msgs, 
 }
 
 hipError_t launch_store_update(uint32_t *W, int C, int L, int nw, const int32_t *msgs, int64_t M, int32_t *status,
-                               uint32_t *has, uint32_t *Wb, uint64_t *full, hipStream_t s)
+                               char *workspace, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
+    const Geometry g = geometry(C, L);
+    uint32_t *Wb = reinterpret_cast<uint32_t *>(workspace);
+    uint32_t *has = reinterpret_cast<uint32_t *>(workspace + workspace_has_offset(C, L));
+    uint64_t *full = reinterpret_cast<uint64_t *>(workspace + workspace_full_offset(C, L));
+    uint32_t *hasc = g.padded ? reinterpret_cast<uint32_t *>(workspace + workspace_canonical_offset(C, L)) : nullptr;
     const int64_t total = M * C;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_store_update, dim3((unsigned)blocks), dim3(256), 0, s, W, Wb, has, C, L, nw, msgs, M, status);
+    hipLaunchKernelGGL(k_store_update, dim3((unsigned)blocks), dim3(256), 0, s, W, Wb, has, hasc, C, L, nw, g.Lp, g.nwp,
+                       msgs, M, status);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, C * L, nw, full);
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, L, g.Lp, g.np, g.nwp, full);
     return hipGetLastError();
 }
 
@@ -309,22 +361,41 @@ hipError_t launch_summary(const uint32_t *W, int C, int L, int nw, uint32_t *has
     dim3 grid((unsigned)((nw + 63) / 64), (unsigned)C);
     hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, W, C, L, nw, has);
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, C * L, nw, full);
+    if (e != hipSuccess || !full) return e;
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, L, L, C * L, nw, full);
     return hipGetLastError();
 }
 
-hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, uint32_t *has, uint32_t *Wb, uint64_t *full,
-                          hipStream_t s)
+hipError_t launch_prepare(const uint32_t *W, int C, int L, int nw, char *workspace, hipStream_t s)
 {
-    const hipError_t e = launch_summary(W, C, L, nw, has, full, s);
-    if (e != hipSuccess) return e;
-    const int64_t words = (int64_t)C * L * nw;
+    const Geometry g = geometry(C, L);
+    uint32_t *Wb = reinterpret_cast<uint32_t *>(workspace);
+    uint32_t *has = reinterpret_cast<uint32_t *>(workspace + workspace_has_offset(C, L));
+    uint64_t *full = reinterpret_cast<uint64_t *>(workspace + workspace_full_offset(C, L));
+    const int64_t words = (int64_t)g.np * g.nwp;
     int64_t blocks = (words + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_fill_blocks, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, words, Wb,
-                       Wb + ((int64_t)C * L + C) * nw);
-    return hipGetLastError();
+    if (!g.padded) {
+        const hipError_t e = launch_summary(W, C, L, nw, has, full, s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_fill_blocks, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, words, Wb,
+                           Wb + ((int64_t)g.np + C) * g.nwp);
+        return hipGetLastError();
+    }
+    // padded: the table first, then its summaries from the table itself (a padded network in its own canonical
+    // layout: clusters of Lp neurons), then the summaries in the interface's layout for the any-shape kernel
+    hipLaunchKernelGGL(k_fill_padded, dim3((unsigned)blocks), dim3(256), 0, s, W, L, nw, g.Lp, g.nwp, words, Wb,
+                       Wb + ((int64_t)g.np + C) * g.nwp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((g.nwp + 63) / 64), (unsigned)C);
+    hipLaunchKernelGGL(k_cluster_summary, grid, dim3(64 * kSumRows), 0, s, Wb, C, g.Lp, g.nwp, has);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_summary_full, dim3(1), dim3(1024), 0, s, has, C, L, g.Lp, g.np, g.nwp, full);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_summary(W, C, L, nw, reinterpret_cast<uint32_t *>(workspace + workspace_canonical_offset(C, L)), nullptr, s);
 }
 
 }  // namespace gbnn

@@ -149,7 +149,11 @@ def test_strerror_and_path(lib):
     assert gb.gbnn_retrieve_path(64, 32, "sum_of_max") == "wave1"
     assert gb.gbnn_retrieve_path(16, 512, "hybrid") == "wave4"
     assert gb.gbnn_retrieve_path(12, 256, "hybrid") == "wave2"
-    assert gb.gbnn_retrieve_path(4, 16, "sum_of_max") == "generic"
+    assert gb.gbnn_retrieve_path(4, 16, "sum_of_max") == "half1"       # clusters padded to 32 neurons
+    assert gb.gbnn_retrieve_path(8, 100, "hybrid") == "half1"          # ... to 128
+    assert gb.gbnn_retrieve_path(10, 300, "sum_of_sum") == "wave4"     # ... to 512
+    assert gb.gbnn_retrieve_path(60, 270, "sum_of_max") == "generic"   # 60 x 512 neurons would exceed the limit
+    assert gb.gbnn_retrieve_path(3, 2049, "sum_of_max") == "generic"   # no more than 2048 neurons per cluster
     assert gb.gbnn_retrieve_path(16, 1024, "sum_of_max") == "wave8"
     assert gb.gbnn_retrieve_path(8, 2048, "hybrid") == "wave8"
     assert gb.gbnn_retrieve_path(16, 1024, "sum_of_sum") == "wave8"

@@ -163,6 +163,15 @@ SHAPES = [
     (8, 256, 300, 4, 130),     # a nearly empty network: no cluster summary is all ones (none may be skipped)
     (8, 128, 100, 5, 131),     # ... two probes per wave
     (8, 256, 3000, 4, 130),    # ... some summaries all ones, some not
+    # cluster sizes that are not a power of two (or below 32): padded clusters in the register kernels
+    (8, 100, 3000, 4, 301),    # 100 -> 128: two probes per wave; activity in 4-byte pieces
+    (8, 200, 12000, 4, 203),   # 200 -> 256: one word per lane; 8-byte-aligned clusters
+    (12, 96, 3000, 6, 150),    # 96 -> 128: whole words of the packed result change places
+    (10, 300, 30000, 5, 77),   # 300 -> 512: four words per lane
+    (6, 700, 90000, 3, 41),    # 700 -> 1024: four words per lane, odd alignment of the clusters (4 bytes)
+    (5, 1501, 200000, 2, 23),  # 1501 -> 2048: eight words per lane, byte-wise activity
+    (9, 17, 120, 4, 130),      # 17 -> 32: clusters share the words of the packed result
+    (40, 50, 900, 20, 61),     # 50 -> 64: 80 words, two per lane
 ]
 
 
@@ -260,7 +269,9 @@ def test_messages_at_the_boundary_edge_cases(networks):
                                     (16, 512, 100000), (32, 32, 700), (2, 512, 30000), (12, 256, 20000),
                                     # eight words per lane: sum-of-sum digits beyond the registers, the hybrid's
                                     # signal counter and the crowded-cluster walk at that width
-                                    (16, 1024, 60000), (8, 2048, 40000), (64, 256, 8000), (9, 1024, 30000)])
+                                    (16, 1024, 60000), (8, 2048, 40000), (64, 256, 8000), (9, 1024, 30000),
+                                    # padded clusters
+                                    (8, 100, 3000), (8, 200, 12000), (10, 300, 30000), (9, 17, 120), (3, 3, 12)])
 @pytest.mark.parametrize("rule", RULES)
 def test_arbitrary_binary_probes(networks, C, L, M, rule):
     """Probes outside the one-active-neuron-per-cluster contract: several active neurons in a
@@ -368,7 +379,7 @@ def test_edge_cases(networks):
                 check_same(out, it, ref, itref, f"e={e} {rule} cap={cap}")
                 out, it = dev_retrieve(Wd, C, L, V0, rule, 1, cap, force_wave=True)
                 check_same(out, it, ref, itref, f"e={e} {rule} cap={cap} wave")
-    # in place, without iters_out; then through an unaligned view (any-shape kernel)
+    # in place, without iters_out; then through an unaligned view
     q, er = inputs.make_probe_plan(C, M, 77, 4, 10)
     V0 = inputs.one_hot(msgs[q], L, er)
     ref, itref, _ = orc.retrieve(Wo, C, L, V0, "sum_of_max", 1, 20)
@@ -378,7 +389,7 @@ def test_edge_cases(networks):
     raw = torch.zeros(V0.size + 64, dtype=torch.uint8, device="cuda")
     view = raw[3:3 + V0.size].view(77, n)
     view.copy_(torch.from_numpy(V0))
-    assert gb.gbnn_retrieve_path(C, L, "hybrid", view, view) == "generic"
+    assert gb.gbnn_retrieve_path(C, L, "hybrid", view, view) == "wave1"   # (byte-wise loads and stores of the activity)
     refh, ith, _ = orc.retrieve(Wo, C, L, V0, "hybrid", 1, 20)
     out, it = gb.gbnn_retrieve(Wd, C, L, view, "hybrid", 1, 20, V_out=view)
     torch.cuda.synchronize()
