@@ -615,14 +615,47 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
         // (more words per lane: the networks whose table exceeds an L2; four at a time measured best there)
         A = 0u;
         for (int i0 = 0; i0 < T; i0 += 4) A |= gather_bits<4>(x, woff, offv, i0, bitpos, true) << i0;
-    } else if (T <= 8) {
-        A = gather_bits<8>(x, woff, offv, 0, bitpos, inl);
-    } else if (T <= 16) {
-        A = gather_bits<16>(x, woff, offv, 0, bitpos, inl);
-    } else if (T <= 24) {
-        A = gather_bits<24>(x, woff, offv, 0, bitpos, inl);
     } else {
-        A = gather_bits<32>(x, woff, offv, 0, bitpos, inl);
+        // W is symmetric (Section IV-B): the adjacency of candidates q and q' can be read from the row of either.
+        // The rows of one cluster's candidates are therefore not fetched at all -- those of the longest run D
+        // = [Ds, De) of positions: every pair with one end in D is read from the row of the other end (the
+        // lanes of D take part in those loads like all others), and the bits obtained there are copied to
+        // the other side afterwards.  What a dense network costs here is the number of loads, not the arithmetic.
+        int Ds = 0, Dn = 0;
+        if (T > 16) {
+            for (uint32_t rem = S; rem;) {
+                const int st = __builtin_ctz(rem);
+                rem &= rem - 1u;
+                const int len = (rem ? __builtin_ctz(rem) : T) - st;
+                if (len > Dn) {
+                    Dn = len;
+                    Ds = st;
+                }
+            }
+            if (Dn < 3) Dn = 0;
+        }
+        const int T2 = T - Dn;  // rows to fetch: positions 0 .. Ds-1 and Ds+Dn .. T-1
+        uint32_t offc = offv;
+        if (Dn)  // close the gap: list position i >= Ds takes the offset of position i + Dn
+            offc = x.lane < Ds ? offv : (uint32_t)__builtin_amdgcn_ds_bpermute((x.lane + Dn) << 2, (int)offv);
+        uint32_t t;
+        if (T2 <= 8)
+            t = gather_bits<8>(x, woff, offc, 0, bitpos, inl);
+        else if (T2 <= 16)
+            t = gather_bits<16>(x, woff, offc, 0, bitpos, inl);
+        else if (T2 <= 24)
+            t = gather_bits<24>(x, woff, offc, 0, bitpos, inl);
+        else
+            t = gather_bits<32>(x, woff, offc, 0, bitpos, inl);
+        A = t;
+        if (Dn) {
+            const uint32_t low = (1u << Ds) - 1u, maskD = ((1u << Dn) - 1u) << Ds;
+            A = (t & low) | ((t & ~low) << Dn);            // bits back at their positions, D left open
+            for (int q = Ds; q < Ds + Dn; ++q) {
+                const uint32_t row_q = readlane(A, q) | maskD;  // candidate q of D: adjacent to candidate q' iff bit q' (own cluster: ones)
+                A |= ((row_q >> x.lane) & 1u) << q;
+            }
+        }
     }
 
     uint32_t m = maskT;          // candidates still on
