@@ -11,7 +11,8 @@ in HBM.  Inputs are seeded synthetic uniform-random messages, the paper's own wo
 The same JSON line carries
   roofline      the dominant kernel of the headline workload: algorithmic bytes per launch over the
                 median of SAMPLES launches bracketed by HIP events on the launch stream, in a loop of
-                its own after the timed region (so that the events do not stretch that region);
+                its own after the timed region (so that the events do not stretch that region), the
+                rules alternating as in a step;
   per_config    the same measurement for every other configuration that has a throughput (cfg2,
                 cfg4 at three M, cfg5), each with a device copy of its probe tensor timed beside it
                 and a sample of its results compared with the CPU oracle;
@@ -102,13 +103,27 @@ def event_samples(torch, fn, count, warm=3):
 
 
 def measure_rules(ld, torch):
-    """Per rule: median / min / mean of SAMPLES event-bracketed launches, and what they mean in bytes."""
+    """Per rule: median / min / mean of SAMPLES launches, each between two HIP events, and what they mean in
+    bytes.  The rules alternate as they do in a step of the timed region (a rule repeated on its own runs in a
+    friendlier cache regime: one result tensor less in the working set)."""
     import numpy as np
     w = ld.w
     abytes = algorithmic_bytes_per_probe(w.n, w.K, True) * w.K
+    evs = {r: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(SAMPLES)]
+           for r in ld.rules}
+    for _ in range(3):
+        for r in ld.rules:
+            ld.call(r)
+    for i in range(SAMPLES):
+        for r in ld.rules:
+            a, b = evs[r][i]
+            a.record()
+            ld.call(r)
+            b.record()
+    torch.cuda.synchronize()
     per_rule = {}
     for r in ld.rules:
-        ms = event_samples(torch, lambda: ld.call(r), SAMPLES)
+        ms = np.array([a.elapsed_time(b) for a, b in evs[r]])
         med = float(np.median(ms))
         per_rule[r] = {"us_median": med * 1e3, "us_min": float(ms.min()) * 1e3, "us_mean": float(ms.mean()) * 1e3,
                        "samples": SAMPLES, "qps": w.K / (med * 1e-3), "hbm_GBs": abytes / (med * 1e-3) / 1e9,
