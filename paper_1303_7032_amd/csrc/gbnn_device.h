@@ -39,6 +39,17 @@ __device__ __forceinline__ uint4 spread16(uint32_t h)
     return make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4((h >> 12) & 15u));
 }
 
+// Bits of word w (neurons 32w .. 32w+31) that lie in cluster c = neurons [c*L, (c+1)*L).
+__device__ __forceinline__ uint32_t own_mask(int c, int L, int w)
+{
+    int lo = c * L - 32 * w, hi = lo + L;
+    if (lo < 0) lo = 0;
+    if (hi > 32) hi = 32;
+    if (hi <= lo) return 0u;
+    const uint32_t upto_hi = (hi == 32) ? 0xFFFFFFFFu : ((1u << hi) - 1u);
+    return upto_hi & ~((1u << lo) - 1u);
+}
+
 // Padded clusters: a register kernel holds a cluster of L neurons in Lp / 32 words, Lp = 2^k >= L.  The bits
 // of word number `wi` of a cluster (its neurons 32 wi .. 32 wi + 31) that are neurons at all:
 __device__ __forceinline__ uint32_t pad_mask(uint32_t L, uint32_t wi)

@@ -4,23 +4,11 @@
 // that belong to a cluster.  Lane l owns words l, l+64, ... of every LDS array, so the only
 // cross-lane traffic is the wave-uniform read of activity words and the barriers around it.
 // Same rule definitions as the one-wave-per-probe register kernel; this one favours plainness.
+#include "gbnn_device.h"
 #include "gbnn_internal.h"
 
 namespace gbnn {
 namespace {
-
-constexpr int kPlanes = 16;
-
-// Bits of word w (neurons 32w .. 32w+31) that lie in cluster c = neurons [c*L, (c+1)*L).
-__device__ __forceinline__ uint32_t own_mask(int c, int L, int w)
-{
-    int lo = c * L - 32 * w, hi = lo + L;
-    if (lo < 0) lo = 0;
-    if (hi > 32) hi = 32;
-    if (hi <= lo) return 0u;
-    const uint32_t upto_hi = (hi == 32) ? 0xFFFFFFFFu : ((1u << hi) - 1u);
-    return upto_hi & ~((1u << lo) - 1u);
-}
 
 __device__ __forceinline__ int wave_sum(int x)
 {

@@ -179,17 +179,6 @@ __global__ __launch_bounds__(kStoreThreads) void k_store_rows(uint32_t *W, int C
     }
 }
 
-// Bits of word w (neurons 32w .. 32w+31) that lie in cluster c = neurons [c*L, (c+1)*L).
-__device__ __forceinline__ uint32_t own_mask(int c, int L, int w)
-{
-    int lo = c * L - 32 * w, hi = lo + L;
-    if (lo < 0) lo = 0;
-    if (hi > 32) hi = 32;
-    if (hi <= lo) return 0u;
-    const uint32_t upto_hi = (hi == 32) ? 0xFFFFFFFFu : ((1u << hi) - 1u);
-    return upto_hi & ~((1u << lo) - 1u);
-}
-
 // Cluster summary: has[c][w] = own bits of c | OR over the L rows j of cluster c of W[j][w], i.e.
 // bit i says that neuron i is in c or has at least one neighbour in c.  It is what a fully active
 // cluster (the sum-of-max initialisation of an erased cluster, Section III-C) lets survive.
