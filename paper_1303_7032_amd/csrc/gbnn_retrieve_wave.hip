@@ -606,16 +606,47 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
     const uint32_t bitpos = jq & 31u;
     const uint32_t offv = __umul24(jq, x.rowbytes);
 
-    // A: lane q reads, from the row of every candidate q', the one word that holds its own bit.  All
-    // loads are issued before the first is waited for (a probe's time is its chain of memory round trips),
-    // in a batch of 8, 16, 24 or 32; positions past T repeat the last candidate.  Only the lanes that hold
-    // a candidate take part: the address unit works through a load 16 lanes at a time and skips idle ones.
+    // A: lane q reads, from the row of a candidate q', the one word that holds its own bit.  The loads of a
+    // batch are issued before the first is waited for (a probe's time is its chain of memory round trips), and
+    // only the lanes that need the word take part: the address unit works through a load 16 lanes at a time
+    // and skips idle ones.
     uint32_t A;
     if (NW > 1) {
-        // (more words per lane: the networks whose table exceeds an L2; four at a time measured best there)
+        // More words per lane: networks whose table exceeds an L2, so that every fetched word costs a line
+        // over the fabric.  W is symmetric (Section IV-B): of every pair of candidates only the later one reads
+        // (q' < q, from the row of the earlier one), pairs within a cluster are not read at all (ones), and the
+        // other half of A is the transpose of what was read.
+        const int Tr = 31 - __builtin_clz(S);   // first position of the last run: the rows of its candidates are never read
         A = 0u;
-        for (int i0 = 0; i0 < T; i0 += 4) A |= gather_bits<4>(x, woff, offv, i0, bitpos, true) << i0;
+        constexpr int TB = 8;   // loads in flight together
+        for (int i0 = 0; i0 < Tr; i0 += TB) {
+            uint32_t so[TB], cs[TB], w[TB];
+#pragma unroll
+            for (int q = 0; q < TB; ++q) {
+                so[q] = readlane(offv, i0 + q);
+                cs[q] = readlane(cq, i0 + q);
+                w[q] = 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < TB; ++q)
+                if (inl && x.lane > i0 + q && cq != cs[q]) w[q] = __builtin_amdgcn_raw_buffer_load_b32(x.wbrsrc, woff, so[q], 0);
+#pragma unroll
+            for (int q = 0; q < TB; ++q) A |= ((w[q] >> bitpos) & 1u) << ((i0 + q) & 31);   // idle lanes: w = 0
+        }
+        for (int q = 1; q < T; ++q) {
+            const uint32_t row_q = readlane(A, q);    // bits q' < q of candidate q
+            A |= ((row_q >> (x.lane & 31)) & 1u) << q;
+        }
+        {   // own cluster: ones from the first to the last position of the lane's run
+            const uint32_t upto = 0xFFFFFFFFu >> (31 - (x.lane & 31));                 // positions 0 .. lane
+            const int st = 31 - __builtin_clz((S & upto) | 1u);
+            const uint32_t after = E & ~(upto >> 1);                                    // run ends at or after lane
+            const int en = after ? __builtin_ctz(after) : 31;
+            A |= (0xFFFFFFFFu >> (31 - en)) & (0xFFFFFFFFu << st);
+        }
     } else {
+        // One word per lane (the table stays in the L2s): batches of 8, 16, 24 or 32 loads, every candidate's lane
+        // taking part; positions past T repeat the last candidate.
         // W is symmetric (Section IV-B): the adjacency of candidates q and q' can be read from the row of either.
         // The rows of one cluster's candidates are therefore not fetched at all -- those of the longest run D
         // = [Ds, De) of positions: every pair with one end in D is read from the row of the other end (the
