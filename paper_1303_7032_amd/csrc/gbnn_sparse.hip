@@ -145,13 +145,14 @@ struct SparseArgs {
 
 constexpr int kSparseList = 128;  // neurons listed at a time
 
-// LDS of one wave: cur[nw] (the activity vector, for the per-cluster statistics), nlist[kSparseList],
+// LDS of one wave: cur[nw] (the final vector, for the symbols), nlist[kSparseList],
 // T[group][nw].
 __host__ __device__ inline int sparse_wave_words(int nw, int group) { return nw + kSparseList + group * nw; }
 
 // NS = words of the activity vector per lane (1, 2, 4 or 8: nw <= 64 NS).
 template <int NS>
-__global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArgs a)
+__global__ __launch_bounds__(64 * kSparseWaves) __attribute__((amdgpu_waves_per_eu(NS == 8 ? 4 : NS == 4 ? 6 : 8))) void
+k_retrieve_sparse(SparseArgs a)
 {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x & 63;
@@ -184,26 +185,32 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
     int32_t iters = 0;
     for (int p = 1;; ++p) {
         // per cluster: number of active neurons, and whether any changed in the pass before
+        uint64_t emptym, fullm, srcm;
+        if (p == 1) {
+            // as the probe arrives: a known cluster holds one neuron, an erased one all of its L >= 32
+            const bool erased = lane < C && (uint32_t)a.sym_in[k * C + lane] >= (uint32_t)L;
+            emptym = 0;
+            fullm = ballot(erased);
+            srcm = ballot(lane < C);
+        } else {
+            // every lane adds what its words hold to the slots of their clusters (T[0 .. C) and T[C .. 2C))
+            if (lane < C) {
+                T[lane] = 0u;
+                T[C + lane] = 0u;
+            }
+            wave_lds_sync();
 #pragma unroll
-        for (int u = 0; u < NS; ++u) {
-            const int w = lane + 64 * u;
-            if (w < nw) {
-                cur[w] = v[u];
-                T[w] = d[u];
+            for (int u = 0; u < NS; ++u) {
+                if (cl[u] >= 0 && v[u]) atomicAdd(&T[cl[u]], (uint32_t)__popc(v[u]));
+                if (cl[u] >= 0 && d[u]) atomicOr(&T[C + cl[u]], 1u);
             }
+            wave_lds_sync();
+            const uint32_t cnt = lane < C ? T[lane] : 0u, chg = lane < C ? T[C + lane] : 0u;
+            emptym = ballot(lane < C && cnt == 0u);
+            fullm = ballot(lane < C && cnt == (uint32_t)L);
+            srcm = ballot(lane < C && chg != 0u);
+            wave_lds_sync();
         }
-        wave_lds_sync();
-        uint32_t cnt = 0, chg = 0;
-        if (lane < C) {
-            for (int i = 0; i < wpc; ++i) {
-                cnt += __popc(cur[lane * wpc + i]);
-                chg |= T[lane * wpc + i];
-            }
-        }
-        const uint64_t emptym = ballot(lane < C && cnt == 0u);
-        const uint64_t fullm = ballot(lane < C && cnt == (uint32_t)L);
-        uint64_t srcm = p == 1 ? ballot(lane < C) : ballot(lane < C && chg != 0u);
-        wave_lds_sync();
 #pragma unroll
         for (int u = 0; u < NS; ++u) acc[u] = emptym ? 0u : v[u];
         if (emptym) srcm = 0;  // a cluster without an active neuron: nobody reaches C - 1 clusters
@@ -219,12 +226,18 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
         // the other clusters to walk, as many at a time as have their bit vectors T in LDS together
         uint64_t walk = srcm & ~fullm;
         while (walk) {
-            uint64_t grp = 0;
-            for (int g = 0; g < a.group && walk; ++g) {
-                grp |= walk & (0ull - walk);
-                walk &= walk - 1ull;
+            uint64_t grp = walk;
+            int ng = __builtin_popcountll(grp);
+            if (ng > a.group) {  // more clusters than bit vectors: the lowest a.group of them now
+                grp = 0;
+                for (int g = 0; g < a.group; ++g) {
+                    grp |= walk & (0ull - walk);
+                    walk &= walk - 1ull;
+                }
+                ng = a.group;
+            } else {
+                walk = 0;
             }
-            const int ng = __builtin_popcountll(grp);
             for (int i = lane; i < ng * nw; i += 64) T[i] = 0u;
             // the active neurons of these clusters, and for each the row of T its list goes to
             uint32_t pw[NS], trow[NS];
@@ -285,12 +298,15 @@ __global__ __launch_bounds__(64 * kSparseWaves) void k_retrieve_sparse(SparseArg
 #pragma unroll
                             for (int q = 0; q < 2; ++q) {
                                 const uint32_t t = t0 + q * step;
+                                if (q == 1 && t >= end) break;  // (short lists: most lanes have one chunk)
+                                // entries t .. t + 7, of which [beg, end) belong to the list
+                                const uint32_t lo = beg > t ? beg - t : 0u, hi = end - t < 8u ? end - t : 8u;
+                                const uint32_t live = (0xFFu >> (8u - hi)) & (0xFFu << lo);
                                 const uint32_t wd[4] = {ch[q].x, ch[q].y, ch[q].z, ch[q].w};
 #pragma unroll
                                 for (int e = 0; e < 8; ++e) {
-                                    const uint32_t col = (wd[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-                                    const uint32_t idx = t + (uint32_t)e;
-                                    if (idx >= beg && idx < end && col < (uint32_t)a.n) atomicOr(&Tr[col >> 5], 1u << (col & 31u));
+                                    const uint32_t col = (e & 1) ? wd[e >> 1] >> 16 : wd[e >> 1] & 0xFFFFu;
+                                    if (((live >> e) & 1u) && col < (uint32_t)a.n) atomicOr(&Tr[col >> 5], 1u << (col & 31u));
                                 }
                             }
                         }
