@@ -69,6 +69,13 @@ __device__ __forceinline__ void store16_unaligned(uint8_t *p, uint4 s)
     u32x4_unaligned x = {s.x, s.y, s.z, s.w};
     *reinterpret_cast<u32x4_unaligned *>(p) = x;
 }
+// 16 bytes to a 16-byte aligned address, non-temporal: not kept in the caches on the way to memory.
+typedef uint32_t u32x4_aligned __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_nontemporal(uint8_t *p, uint4 s)
+{
+    const u32x4_aligned x = {s.x, s.y, s.z, s.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<u32x4_aligned *>(p));
+}
 // The first `count` (< 16) of 16 bytes, the rest zero: byte loads, none past the last one asked for.
 __device__ __forceinline__ uint4 load_bytes(const uint8_t *p, uint32_t count)
 {

@@ -674,15 +674,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
             const int32_t sy = cluster_symbol<LGL>(v, x.gl & kInCluster);
             if (x.islead) a.sym_out[probe_offset(k0, a.C) + second * a.C + x.myc] = sy;
         }
+    } else if (plain_io) {
+        // A half's words are 32 nw bytes: written as two contiguous pieces, lane j of the half storing 16 bytes at
+        // 16 j of each -- half (j & 1) of the word of lane j / 2 (first piece) and of lane 16 + j / 2 (second
+        // piece) -- so that every store instruction covers whole lines; non-temporal, as the results are not
+        // read again and should not displace the table and the probes in the caches.
+        const uint32_t wa = entry(v, x.basev + ((x.gl >> 1) << 2));
+        const uint32_t wb = entry(v, x.basev + ((16u + (x.gl >> 1)) << 2));
+        const uint32_t sh = (x.gl & 1u) * 16u;
+        uint8_t *piece = a.Vout + probe_offset(k0, a.n) + (upper ? (uint32_t)a.n : 0u) + 16u * x.gl;
+        if (pvalid && (x.gl >> 1) < (uint32_t)a.nw) store16_nontemporal(piece, spread16((wa >> sh) & 0xFFFFu));
+        if (pvalid && 16u + (x.gl >> 1) < (uint32_t)a.nw) store16_nontemporal(piece + 512, spread16((wb >> sh) & 0xFFFFu));
     } else if (x.valid) {
-        if (plain_io) {
-            uint4 *dst = reinterpret_cast<uint4 *>(a.Vout + probe_offset(k0, a.n) + boff);
-            dst[0] = spread16(v & 0xFFFFu);
-            dst[1] = spread16(v >> 16);
-        } else {
-            store_cluster_word(a.Vout + probe_offset(kmine, a.n) + x.myc * (uint32_t)a.L, (uint32_t)a.L, x.gl & kInCluster,
-                               a.align >= 4, v);
-        }
+        store_cluster_word(a.Vout + probe_offset(kmine, a.n) + x.myc * (uint32_t)a.L, (uint32_t)a.L, x.gl & kInCluster,
+                           a.align >= 4, v);
     }
 }
 
