@@ -76,6 +76,11 @@ __device__ __forceinline__ void store16_nontemporal(uint8_t *p, uint4 s)
     const u32x4_aligned x = {s.x, s.y, s.z, s.w};
     __builtin_nontemporal_store(x, reinterpret_cast<u32x4_aligned *>(p));
 }
+__device__ __forceinline__ uint4 load16_nontemporal(const uint8_t *p)
+{
+    const u32x4_aligned x = __builtin_nontemporal_load(reinterpret_cast<const u32x4_aligned *>(p));
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
 // The first `count` (< 16) of 16 bytes, the rest zero: byte loads, none past the last one asked for.
 __device__ __forceinline__ uint4 load_bytes(const uint8_t *p, uint32_t count)
 {

@@ -780,10 +780,26 @@ k_retrieve_wave(RetrieveArgs a)
             const uint8_t *src = a.V0 + probe_offset(k, a.n);
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
-                const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
-                const uint4 lo = p[0];
-                const uint4 hi = p[1];
-                v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
+                if (a.stream_in) {
+                    // two contiguous pieces of 1 KiB per slot (lane j reads 16 bytes at 16 j of each: half (j & 1)
+                    // of word j / 2, and of word 32 + j / 2), non-temporal; the lanes then collect their words
+                    const uint32_t first = 64u * t + ((uint32_t)x.lane >> 1);
+                    const uint8_t *piece = src + 2048u * t + 16u * (uint32_t)x.lane;
+                    uint4 pa = make_uint4(0u, 0u, 0u, 0u), pb = pa;
+                    if (first < (uint32_t)a.nw) pa = load16_nontemporal(piece);
+                    if (first + 32u < (uint32_t)a.nw) pb = load16_nontemporal(piece + 1024);
+                    const uint32_t m = pack16(pa) | (pack16(pb) << 16);
+                    const int s0 = (x.lane & 31) << 1;
+                    const uint32_t x0 = (uint32_t)__builtin_amdgcn_ds_bpermute(s0 << 2, (int)m);
+                    const uint32_t x1 = (uint32_t)__builtin_amdgcn_ds_bpermute((s0 + 1) << 2, (int)m);
+                    v[t] = x.lane < 32 ? (x0 & 0xFFFFu) | (x1 << 16) : (x0 >> 16) | (x1 & 0xFFFF0000u);
+                    if (!x.valid[t]) v[t] = 0u;
+                } else {
+                    const uint4 *p = reinterpret_cast<const uint4 *>(src + x.woffb[t] * 8u);
+                    const uint4 lo = p[0];
+                    const uint4 hi = p[1];
+                    v[t] = x.valid[t] ? (pack16(lo) | (pack16(hi) << 16)) : 0u;
+                }
             }
         } else {
             const uint8_t *src = a.V0 + probe_offset(k, a.n);

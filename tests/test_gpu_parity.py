@@ -476,3 +476,33 @@ def test_full_configuration(name):
         del padded, act
     if "hybrid" in finals and "sum_of_max" in finals:
         assert (finals["hybrid"] == finals["sum_of_max"]).all()      # Theorem 4
+
+
+def test_streamed_probe_loads_with_a_partly_filled_slot():
+    """A batch of more than 512 MiB on a table larger than an L2 is read with the streaming loads (two
+    contiguous pieces per 64 words, lanes exchanging half words); here the last slot of a lane holds words
+    only in 8 of 64 lanes (25 x 256: 200 packed words).  All probes against the any-shape kernel, the first
+    1024 against the oracle."""
+    C, L, M, e = 25, 256, 30000, 12
+    K = (513 << 20) // (C * L) + 1
+    assert K * C * L >= 512 << 20
+    msgs = inputs.make_messages(C, L, M, 91)
+    Wo, _ = orc.store(C, L, msgs)
+    Wd, _ = dev_store(C, L, msgs)
+    q, er = inputs.make_probe_plan(C, M, K, e, 92)
+    idx = torch.from_numpy(inputs.active_neurons(msgs[q], L)).cuda()
+    V0d = torch.zeros((K, C * L), dtype=torch.uint8, device="cuda")
+    V0d.scatter_(1, idx, torch.from_numpy((~er).astype(np.uint8)).cuda())
+    del idx
+    host = V0d[:1024].cpu().numpy()
+    for rule in ("sum_of_max", "hybrid"):
+        assert gb.gbnn_retrieve_path(C, L, rule, V0d) == "wave4"
+        out, it = gb.gbnn_retrieve(Wd, C, L, V0d, rule, 1, 20)
+        with family(force_generic=True):
+            out2, it2 = gb.gbnn_retrieve(Wd, C, L, V0d, rule, 1, 20)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2) and torch.equal(it, it2), rule
+        ref, itref, _ = orc.retrieve(Wo, C, L, host, rule, 1, 20)
+        check_same(out[:1024].cpu().numpy(), it[:1024].cpu().numpy(), ref, itref, f"streamed loads {rule}")
+        del out, out2
+
