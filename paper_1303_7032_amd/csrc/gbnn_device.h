@@ -81,6 +81,11 @@ __device__ __forceinline__ uint4 load16_nontemporal(const uint8_t *p)
     const u32x4_aligned x = __builtin_nontemporal_load(reinterpret_cast<const u32x4_aligned *>(p));
     return make_uint4(x.x, x.y, x.z, x.w);
 }
+__device__ __forceinline__ void store16_unaligned_nontemporal(uint8_t *p, uint4 s)
+{
+    const u32x4_unaligned x = {s.x, s.y, s.z, s.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<u32x4_unaligned *>(p));
+}
 // The first `count` (< 16) of 16 bytes, the rest zero: byte loads, none past the last one asked for.
 __device__ __forceinline__ uint4 load_bytes(const uint8_t *p, uint32_t count)
 {
@@ -109,35 +114,10 @@ __device__ __forceinline__ uint32_t load_cluster_word(const uint8_t *cl, uint32_
     }
     return (pack16(p[0]) | (pack16(p[1]) << 16)) & pad_mask(L, wi);
 }
-// ... and back: the 32 bits of v as bytes cl[32 wi ..], those within the cluster only.  Whole 16-byte pieces
-// at any alignment; a piece cut short by the end of the cluster in 4-byte pieces if `by4` (cl and L are
-// multiples of 4), else byte by byte.
-__device__ __forceinline__ void store_cluster_word(uint8_t *cl, uint32_t L, uint32_t wi, bool by4, uint32_t v)
-{
-    const uint32_t l0 = 32u * wi;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const uint32_t at = l0 + 16u * h;
-        const uint4 s = spread16((v >> (16 * h)) & 0xFFFFu);
-        if (at + 16u <= L) {
-            store16_unaligned(cl + at, s);
-        } else if (at < L) {
-            const uint32_t d[4] = {s.x, s.y, s.z, s.w};
-            if (by4) {
-#pragma unroll
-                for (int q = 0; q < 3; ++q)
-                    if (at + 4u * q < L) *reinterpret_cast<uint32_t *>(cl + at + 4 * q) = d[q];
-            } else {
-#pragma unroll
-                for (int b = 0; b < 15; ++b)
-                    if (at + (uint32_t)b < L) cl[at + b] = (uint8_t)(d[b >> 2] >> (8 * (b & 3)));
-            }
-        }
-    }
-}
-// The packed result of a padded kernel at the message boundary when clusters share words of it (L not a
-// multiple of 32): word `wi` of cluster c, value v (bits past the end of the cluster are zero), ORed into the
-// canonical bit positions c*L + 32 wi .. of a bit vector in LDS that the wave has zeroed.
+// On the way from a padded kernel's words to the canonical layout (the packed output of the message boundary
+// when clusters share words, the byte output of the activity boundary): word `wi` of cluster c, value v (bits
+// past the end of the cluster are zero), ORed into the canonical bit positions c*L + 32 wi .. of a bit vector
+// in LDS that the wave has zeroed.
 __device__ __forceinline__ void or_cluster_word(uint32_t *out, uint32_t c, uint32_t L, uint32_t wi, uint32_t v)
 {
     if (32u * wi >= L || v == 0u) return;

@@ -685,9 +685,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
         uint8_t *piece = a.Vout + probe_offset(k0, a.n) + (upper ? (uint32_t)a.n : 0u) + 16u * x.gl;
         if (pvalid && (x.gl >> 1) < (uint32_t)a.nw) store16_nontemporal(piece, spread16((wa >> sh) & 0xFFFFu));
         if (pvalid && 16u + (x.gl >> 1) < (uint32_t)a.nw) store16_nontemporal(piece + 512, spread16((wb >> sh) & 0xFFFFu));
-    } else if (x.valid) {
-        store_cluster_word(a.Vout + probe_offset(kmine, a.n) + x.myc * (uint32_t)a.L, (uint32_t)a.L, x.gl & kInCluster,
-                           a.align >= 4, v);
+    } else {
+        // Padded clusters, or buffers that are not 16-byte aligned: each half puts its canonical bit vector together
+        // in LDS and writes the n bytes of its result front to back, 16 bytes per lane and step at whatever
+        // alignment the result has (non-temporal as above); the last n mod 16 bytes one by one.
+        uint32_t *canon = lds_words + (threadIdx.x >> 6) * (kLdsWords / 4) + (upper ? 32u : 0u);
+        if (x.gl < (uint32_t)a.nw) canon[x.gl] = 0u;
+        wave_lds_sync();
+        if (x.valid) or_cluster_word(canon, x.myc, (uint32_t)a.L, x.gl & kInCluster, v);
+        wave_lds_sync();
+        if (pvalid) {
+            uint8_t *dstb = a.Vout + probe_offset(kmine, a.n);
+            const uint16_t *canon16 = reinterpret_cast<const uint16_t *>(canon);
+            const uint32_t pieces = (uint32_t)a.n >> 4;
+            for (uint32_t j = x.gl; j < pieces; j += 32u) store16_unaligned_nontemporal(dstb + 16u * j, spread16(canon16[j]));
+            const uint32_t i = (pieces << 4) + x.gl;
+            if (x.gl < ((uint32_t)a.n & 15u)) dstb[i] = (uint8_t)((canon[i >> 5] >> (i & 31u)) & 1u);
+        }
     }
 }
 

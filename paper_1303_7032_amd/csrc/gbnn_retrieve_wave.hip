@@ -1042,12 +1042,23 @@ k_retrieve_wave(RetrieveArgs a)
                 }
             }
         } else {
+            // Padded clusters, or buffers that are not 16-byte aligned: the canonical bit vector is put together in
+            // LDS (as for the packed output above) and the wave writes the n bytes of the result front to back,
+            // 16 neurons = 16 bytes per lane and step at whatever alignment the result has, non-temporal like the
+            // aligned stores; the last n mod 16 bytes one by one.
             uint8_t *dstb = a.Vout + probe_offset(k, a.n);
+            uint32_t *canon = lds_words + (threadIdx.x >> 6) * (kLdsWords / 4);
+            for (int w = x.lane; w < a.nw; w += 64) canon[w] = 0u;
+            wave_lds_sync();
 #pragma unroll
             for (int t = 0; t < NW; ++t)
-                if (x.valid[t])
-                    store_cluster_word(dstb + x.myc[t] * (uint32_t)a.L, (uint32_t)a.L, (uint32_t)x.lane & (LW - 1),
-                                       a.align >= 4, v[t]);
+                if (x.valid[t]) or_cluster_word(canon, x.myc[t], (uint32_t)a.L, (uint32_t)x.lane & (LW - 1), v[t]);
+            wave_lds_sync();
+            const uint16_t *canon16 = reinterpret_cast<const uint16_t *>(canon);
+            const int pieces = a.n >> 4;
+            for (int j = x.lane; j < pieces; j += 64) store16_unaligned_nontemporal(dstb + 16 * j, spread16(canon16[j]));
+            const int i = (pieces << 4) + x.lane;
+            if (x.lane < (a.n & 15)) dstb[i] = (uint8_t)((canon[i >> 5] >> (i & 31)) & 1u);
         }
     }
 }
