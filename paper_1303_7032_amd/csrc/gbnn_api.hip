@@ -78,8 +78,7 @@ int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K,
     a.has = reinterpret_cast<const uint32_t *>(ws + workspace_has_offset(C, L));
     a.hasc = g.padded ? reinterpret_cast<const uint32_t *>(ws + workspace_canonical_offset(C, L)) : a.has;
     a.full = reinterpret_cast<const uint64_t *>(ws + workspace_full_offset(C, L));
-    a.align = (L % 16 == 0 && aligned(a.V0, 16) && aligned(a.Vout, 16)) ? 16
-              : (L % 4 == 0 && aligned(a.V0, 4) && aligned(a.Vout, 4)) ? 4 : 1;
+    a.aligned16 = L % 16 == 0 && aligned(a.V0, 16) && aligned(a.Vout, 16);
     // Probes that cannot stay in the 256 MB memory-side cache from one call to the next anyway are read with
     // non-temporal loads where the table is larger than one of the 4 MiB L2s: the table then keeps more of the
     // L2 (16x512, K=131072: 402 -> 388 us).  A batch that fits the memory-side cache is read faster without

@@ -45,7 +45,7 @@ struct RetrieveArgs {
     int64_t K;
     int C, L, n, nw;      // the network as the interface sees it
     int Lp, np, nwp;      // ... and as the register kernels do (geometry())
-    int align;            // 16, 4 or 1: what V0, Vout and L are all multiples of (activity boundary)
+    bool aligned16;       // V0, Vout and L are all multiples of 16 (activity boundary)
     bool stream_in;       // read the probes with streaming loads (see retrieve_common)
     int rule, gamma, max_iters;
 };

@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void k
     const uint32_t boff = (upper ? (uint32_t)a.n : 0u) + x.woffb * 8u;  // this lane's bytes, from the first probe of the pair
     constexpr uint32_t kInCluster = (1u << LGL) - 1u;
     const bool padded = a.Lp != a.L;  // clusters of L neurons held in the words of Lp = 2^k > L
-    const bool plain_io = !padded && a.align == 16;  // activity as two 16-byte pieces per word, no piece past a cluster's end
+    const bool plain_io = !padded && a.aligned16;  // activity in aligned 16-byte pieces, none past a cluster's end
     // the bits of this lane's word that are neurons (all of them unless the clusters are padded)
     const uint32_t pmask = !x.valid ? 0u : padded ? pad_mask((uint32_t)a.L, x.gl & kInCluster) : 0xFFFFFFFFu;
     uint32_t v;

@@ -749,7 +749,7 @@ k_retrieve_wave(RetrieveArgs a)
                                                  (int)((uint32_t)(a.np + a.C + kTableExtraRows) * x.rowbytes), 0x00020000);
     x.lane = threadIdx.x & 63;
     const bool padded = a.Lp != a.L;  // clusters of L neurons held in the words of Lp = 2^k > L
-    const bool plain_io = !padded && a.align == 16;  // activity as two 16-byte pieces per word, no piece past a cluster's end
+    const bool plain_io = !padded && a.aligned16;  // activity in aligned 16-byte pieces, none past a cluster's end
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
         x.valid[t] = (t * 64 + x.lane) < a.nwp;
