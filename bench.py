@@ -15,8 +15,9 @@ The same JSON line carries
                 40 us kernel), in a loop of its own after the timed region (so that the events do not
                 stretch that region), the rules taking turns;
   per_config    the same measurement for every other configuration that has a throughput (cfg2,
-                cfg4 at three M, cfg5), each with a device copy of its probe tensor timed beside it
-                and a sample of its results compared with the CPU oracle;
+                cfg4 at three M, cfg5), each with copies of its probe tensor timed beside it (the
+                framework's, and the library's reference copy kernel with plain and with non-temporal
+                accesses) and a sample of its results compared with the CPU oracle;
   cpu_baseline  the CPU oracle timed on the host cores;
   parity_ok     every sampled result of every workload equals the oracle's.  The exit status is 1
                 when it is false.
@@ -143,6 +144,24 @@ def device_copy(ld, torch):
     return med * 1e3, 2.0 * ld.w.K * ld.w.n / (med * 1e-3) / 1e9
 
 
+def reference_copies(ld, torch):
+    """The library's own copy kernel on the probe tensor (one wavefront per 2 KiB, as the retrieval kernels move
+    activity), with plain and with non-temporal accesses: what the memory system delivers for one read and one
+    write stream of the batch's size.  Microseconds (median of 10 groups of GROUP launches) and GB/s."""
+    import numpy as np
+    scratch = torch.empty_like(ld.V0d)
+    out = {}
+    for name, streaming in (("plain", False), ("streaming", True)):
+        def go():
+            for _ in range(GROUP):
+                ld.gb.gbnn_reference_copy(scratch, ld.V0d, streaming)
+        med = float(np.median(event_samples(torch, go, 10))) / GROUP
+        out[name] = {"us": med * 1e3, "GBs": 2.0 * ld.w.K * ld.w.n / (med * 1e-3) / 1e9}
+    assert torch.equal(scratch, ld.V0d)
+    del scratch
+    return out
+
+
 def outcome(ld, torch):
     """Error rate (exact one-hot match with the source message), mean passes, capped probes, per rule."""
     w = ld.w
@@ -252,6 +271,7 @@ def main() -> int:
             traffic = traffic_detail["total_bytes"]
 
     copy_us, copy_GBs = device_copy(ld, torch)
+    ref_copies = reference_copies(ld, torch)
 
     # ---- reference point: the same retrieval with messages at the boundary (gbnn_retrieve_symbols: symbols in,
     # packed bits + symbols + pass counts out)
@@ -340,6 +360,7 @@ def main() -> int:
             o = Loaded(name, torch, gb, inputs)
             rules_o, abytes_o = measure_rules(o, torch)
             cus, cgbs = device_copy(o, torch)
+            refc = reference_copies(o, torch)
             for r, st in outcome(o, torch).items():
                 rules_o[r].update(st)
                 rules_o[r]["frac_of_device_copy"] = rules_o[r]["hbm_GBs"] / cgbs
@@ -352,6 +373,7 @@ def main() -> int:
                                             f"cap={o.w.max_iters} gamma={o.w.gamma}",
                                 "kernel_path": gb.gbnn_retrieve_path(o.w.C, o.w.L, o.rules[0], o.V0d, o.outs[o.rules[0]]),
                                 "algorithmic_bytes_per_launch": abytes_o, "device_copy_us": cus, "device_copy_GBs": cgbs,
+                                "reference_copy": refc,
                                 "oracle_sample": 0 if args.no_cpu_baseline else min(o.w.K, ORACLE_SAMPLE), "rules": rules_o}
             del o
             gc.collect()
@@ -374,7 +396,7 @@ def main() -> int:
                      "kernel": f"gbnn_retrieve[{dominant}]", "us_median": per_rule[dominant]["us_median"],
                      "event_samples": SAMPLES, "launches_per_sample": GROUP, "algorithmic_bytes_per_launch": abytes,
                      "device_copy_us_same_run": copy_us, "device_copy_GBs_same_run": copy_GBs,
-                     "frac_of_device_copy": achieved / copy_GBs},
+                     "frac_of_device_copy": achieved / copy_GBs, "reference_copy": ref_copies},
         "cpu_baseline": cpu,
         "parity_ok": parity_ok,
         "per_rule": per_rule,

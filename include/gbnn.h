@@ -213,7 +213,7 @@ const char *gbnn_strerror(int code);
  * is not such a number is padded to the next one inside the library (W, activity vectors and results keep
  * their layout, results and pass counts are the same; the workspace grows accordingly).  They serve every
  * shape whose padded network has clusters of at most 2048 and at most GBNN_MAX_N neurons in all, with V0
- * and V_out at any alignment; the any-shape kernel, more than ten times slower, serves the rest. */
+ * and V_out at any alignment; the any-shape kernel, several times slower, serves the rest. */
 const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const void *V_out);
 
 /*
@@ -231,6 +231,17 @@ const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const voi
 enum { GBNN_FAMILY_AUTO = 0, GBNN_FAMILY_GENERIC = 1, GBNN_FAMILY_WAVE = 2 };
 enum { GBNN_STORE_AUTO = 0, GBNN_STORE_ATOMIC = 1, GBNN_STORE_ROWS = 2 };
 int gbnn_set_kernel_choice(int retrieve_family, int store_kernel);
+
+/*
+ * For measurement only, not part of the method: a plain copy of `bytes` bytes from src to dst (both device
+ * pointers, 16-byte aligned; bytes a multiple of 16; the ranges must not overlap), moved the way the retrieval
+ * kernels move activity: one wavefront per 2 KiB, 16 bytes per lane and instruction.  streaming != 0 reads and
+ * writes with non-temporal hints.  The benchmark times it beside the retrieval kernels, as what the memory
+ * system delivers for one read stream and one write stream of a batch's size.  Enqueues on `stream` and
+ * returns; GBNN_ERR_NULL for a null pointer with bytes > 0, GBNN_ERR_SHAPE for a size or pointer that is not
+ * a multiple of 16.
+ */
+int gbnn_reference_copy(void *dst, const void *src, size_t bytes, int streaming, void *stream);
 
 #ifdef __cplusplus
 }

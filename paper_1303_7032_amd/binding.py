@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.gbnn_retrieve_path.argtypes = [ci, ci, ci, vp, vp]
         L.gbnn_set_kernel_choice.restype = ci
         L.gbnn_set_kernel_choice.argtypes = [ci, ci]
+        L.gbnn_reference_copy.restype = ci
+        L.gbnn_reference_copy.argtypes = [vp, vp, sz, ci, vp]
         _lib = L
     return _lib
 
@@ -332,3 +334,15 @@ def gbnn_retrieve_sparse(Wp: torch.Tensor, C: int, L: int, probes: torch.Tensor,
                                       bits_out.data_ptr() if K else 0, symbols_out.data_ptr() if K else 0,
                                       iters_out.data_ptr() if K else 0, _stream(Wp)))
     return bits_out, symbols_out, iters_out
+
+
+def gbnn_reference_copy(dst: torch.Tensor, src: torch.Tensor, streaming: bool) -> None:
+    """dst <- src (same number of bytes, a multiple of 16) by the library's reference copy kernel."""
+    for t, name in ((dst, "dst"), (src, "src")):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise TypeError(f"{name} must be a contiguous tensor on the GPU")
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src differ in size")
+    _check(lib().gbnn_reference_copy(dst.data_ptr(), src.data_ptr(), nbytes, 1 if streaming else 0, _stream(src)))
+

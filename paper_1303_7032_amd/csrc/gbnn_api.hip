@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/gbnn.h: argument checks and kernel dispatch.
 #include <atomic>
 
+#include "gbnn_device.h"
 #include "gbnn_internal.h"
 
 using namespace gbnn;
@@ -101,6 +102,28 @@ int retrieve_common(RetrieveArgs &a, const uint32_t *W, int C, int L, int64_t K,
 }
 
 }  // namespace
+
+namespace gbnn {
+namespace {
+// The reference copy of the benchmark: every wavefront moves 2 KiB, lane l the 16 bytes at 16 l of each KiB.
+template <bool STREAMING>
+__global__ __launch_bounds__(256) void k_reference_copy(const uint8_t *src, uint8_t *dst, size_t bytes)
+{
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t at = wave * 2048 + 16 * (threadIdx.x & 63);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const size_t o = at + 1024 * h;
+        if (o < bytes) {
+            if (STREAMING)
+                store16_nontemporal(dst + o, load16_nontemporal(src + o));
+            else
+                *reinterpret_cast<uint4 *>(dst + o) = *reinterpret_cast<const uint4 *>(src + o);
+        }
+    }
+}
+}  // namespace
+}  // namespace gbnn
 
 extern "C" {
 
@@ -282,6 +305,23 @@ const char *gbnn_retrieve_path(int C, int L, int rule, const void *V0, const voi
     case kHalfPath: return "half1";
     default: return "generic";
     }
+}
+
+int gbnn_reference_copy(void *dst, const void *src, size_t bytes, int streaming, void *stream)
+{
+    if (bytes == 0) return GBNN_OK;
+    if (!dst || !src) return GBNN_ERR_NULL;
+    if (bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return GBNN_ERR_SHAPE;
+    const size_t blocks = (bytes + 8191) / 8192;
+    if (blocks > 0x7FFFFFFFull) return GBNN_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (streaming)
+        hipLaunchKernelGGL(gbnn::k_reference_copy<true>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint8_t *>(src),
+                           static_cast<uint8_t *>(dst), bytes);
+    else
+        hipLaunchKernelGGL(gbnn::k_reference_copy<false>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint8_t *>(src),
+                           static_cast<uint8_t *>(dst), bytes);
+    return hipGetLastError() == hipSuccess ? GBNN_OK : GBNN_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -166,3 +166,14 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(gb, "_LIB_PATH", tmp_path / "missing.so")
     with pytest.raises(FileNotFoundError):
         gb.lib()
+
+
+def test_reference_copy_argument_errors(lib):
+    E = gb.ERRORS
+    assert lib.gbnn_reference_copy(0, 0, 0, 0, 0) == 0                      # nothing to do
+    assert lib.gbnn_reference_copy(0, 0x1000, 16, 0, 0) == E["NULL"]
+    assert lib.gbnn_reference_copy(0x1000, 0, 16, 1, 0) == E["NULL"]
+    assert lib.gbnn_reference_copy(0x1000, 0x2000, 24, 0, 0) == E["SHAPE"]  # not a multiple of 16
+    assert lib.gbnn_reference_copy(0x1008, 0x2000, 32, 0, 0) == E["SHAPE"]  # alignment
+    assert lib.gbnn_reference_copy(0x1000, 0x2004, 32, 1, 0) == E["SHAPE"]
+

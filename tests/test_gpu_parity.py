@@ -506,3 +506,16 @@ def test_streamed_probe_loads_with_a_partly_filled_slot():
         check_same(out[:1024].cpu().numpy(), it[:1024].cpu().numpy(), ref, itref, f"streamed loads {rule}")
         del out, out2
 
+
+@pytest.mark.parametrize("nbytes", [16, 1008, 2048, 2064, 8192 + 48, (1 << 20) + 16])
+@pytest.mark.parametrize("streaming", [False, True])
+def test_reference_copy(nbytes, streaming):
+    """The benchmark's reference copy moves exactly the bytes it is given."""
+    g = torch.Generator(device="cuda").manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes + 32,), dtype=torch.uint8, device="cuda", generator=g)
+    dst = torch.full((nbytes + 32,), 7, dtype=torch.uint8, device="cuda")
+    gb.gbnn_reference_copy(dst[16:16 + nbytes], src[16:16 + nbytes], streaming)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[16:16 + nbytes], src[16:16 + nbytes])
+    assert (dst[:16] == 7).all() and (dst[16 + nbytes:] == 7).all()
+
