@@ -1024,22 +1024,20 @@ k_retrieve_wave(RetrieveArgs a)
             }
         } else if (plain_io) {
             uint8_t *dstb = a.Vout + probe_offset(k, a.n);
+            // The wave's 64 words of a slot are 2 KiB of bytes: written as two contiguous pieces of 1 KiB, lane j
+            // storing 16 bytes at 16 j of each -- half (j & 1) of the word of lane j / 2 (first piece) and of lane
+            // 32 + j / 2 (second piece) -- so that every store instruction covers whole lines, and as non-temporal
+            // stores: the results are not read again, and left out of the caches they do not displace the table
+            // and the probes (cfg3: 52 -> 41 us, cfg5: 443 -> 400 us).
 #pragma unroll
             for (int t = 0; t < NW; ++t) {
-                {
-                    // The wave's 64 words of this slot are 2 KiB of bytes: written as two contiguous pieces of 1 KiB,
-                    // lane j storing 16 bytes at 16 j of each -- half (j & 1) of the word of lane j / 2 (first piece)
-                    // and of lane 32 + j / 2 (second piece) -- so that every store instruction covers whole lines,
-                    // and as non-temporal stores: the results are not read again, and left out of the caches they
-                    // do not displace the table and the probes (cfg3: 52 -> 41 us, cfg5: 443 -> 400 us).
-                    const uint32_t wa = (uint32_t)__builtin_amdgcn_ds_bpermute((x.lane >> 1) << 2, (int)v[t]);
-                    const uint32_t wb = (uint32_t)__builtin_amdgcn_ds_bpermute((32 + (x.lane >> 1)) << 2, (int)v[t]);
-                    const uint32_t sh = (x.lane & 1) * 16;
-                    const uint32_t first = 64u * t + ((uint32_t)x.lane >> 1);  // the word the first piece's bytes come from
-                    uint8_t *piece = dstb + 2048u * t + 16u * (uint32_t)x.lane;
-                    if (first < (uint32_t)a.nw) store16_nontemporal(piece, spread16((wa >> sh) & 0xFFFFu));
-                    if (first + 32u < (uint32_t)a.nw) store16_nontemporal(piece + 1024, spread16((wb >> sh) & 0xFFFFu));
-                }
+                const uint32_t wa = (uint32_t)__builtin_amdgcn_ds_bpermute((x.lane >> 1) << 2, (int)v[t]);
+                const uint32_t wb = (uint32_t)__builtin_amdgcn_ds_bpermute((32 + (x.lane >> 1)) << 2, (int)v[t]);
+                const uint32_t sh = (x.lane & 1) * 16;
+                const uint32_t first = 64u * t + ((uint32_t)x.lane >> 1);  // the word the first piece's bytes come from
+                uint8_t *piece = dstb + 2048u * t + 16u * (uint32_t)x.lane;
+                if (first < (uint32_t)a.nw) store16_nontemporal(piece, spread16((wa >> sh) & 0xFFFFu));
+                if (first + 32u < (uint32_t)a.nw) store16_nontemporal(piece + 1024, spread16((wb >> sh) & 0xFFFFu));
             }
         } else {
             // Padded clusters, or buffers that are not 16-byte aligned: the canonical bit vector is put together in
