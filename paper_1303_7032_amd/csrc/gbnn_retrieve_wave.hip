@@ -645,7 +645,7 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
             A |= (0xFFFFFFFFu >> (31 - en)) & (0xFFFFFFFFu << st);
         }
     } else {
-        // One word per lane (the table stays in the L2s): batches of 8, 16, 24 or 32 loads, every candidate's lane
+        // One word per lane (the table stays in the L2s): one batch of 8, 12, ... 32 loads, every candidate's lane
         // taking part; positions past T repeat the last candidate.
         // W is symmetric (Section IV-B): the adjacency of candidates q and q' can be read from the row of either.
         // The rows of one cluster's candidates are therefore not fetched at all -- those of the longest run D
@@ -672,10 +672,16 @@ __device__ __forceinline__ int candidate_passes(const Ctx<NW> &x, const uint32_t
         uint32_t t;
         if (T2 <= 8)
             t = gather_bits<8>(x, woff, offc, 0, bitpos, inl);
+        else if (T2 <= 12)
+            t = gather_bits<12>(x, woff, offc, 0, bitpos, inl);
         else if (T2 <= 16)
             t = gather_bits<16>(x, woff, offc, 0, bitpos, inl);
+        else if (T2 <= 20)
+            t = gather_bits<20>(x, woff, offc, 0, bitpos, inl);
         else if (T2 <= 24)
             t = gather_bits<24>(x, woff, offc, 0, bitpos, inl);
+        else if (T2 <= 28)
+            t = gather_bits<28>(x, woff, offc, 0, bitpos, inl);
         else
             t = gather_bits<32>(x, woff, offc, 0, bitpos, inl);
         A = t;
